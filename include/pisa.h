@@ -1,0 +1,138 @@
+/*
+ * libpisa -- forward pass of Piecewise Sparse Attention (PISA) for AMD MI355X (gfx950).
+ *
+ * C ABI.  Every entry point below follows one step of the paper's forward-pass
+ * algorithm (Methodology, "Hardware-aware Kernel Implementation", Alg. 1):
+ *
+ *   pisa_block_stats   Alg. 1 line 1   ("Prepare": block means, block value sums, global H)
+ *   pisa_select        Alg. 1 line 2   (block-wise top-k of pooled scores)
+ *   pisa_attention     Alg. 1 lines 4-23 (Phase 1 exact, Phase 2 zeroth-order scan,
+ *                                       Phase 3 global first-order term, one online softmax)
+ *   dense_attention    Preliminaries, first equation (softmax(QK^T/sqrt d)V), the
+ *                      speed-up baseline, written with the same tile loop
+ *
+ * Conventions
+ *   - All tensor pointers are DEVICE pointers owned by the caller; the library never
+ *     allocates, frees or synchronises.  Work is enqueued on `stream`
+ *     (a hipStream_t passed as void*; NULL = the default stream).
+ *   - Layout: Q, K, V, O are dense [batch, heads, seq_len, head_dim], head_dim contiguous.
+ *     Blocks are consecutive runs of `block` tokens; N = ceil(seq_len / block); the last
+ *     block may be ragged (B_j < block rows) -- statistics run over its valid rows.
+ *   - Supported: dtype PISA_BF16 with head_dim 128 (MFMA path); dtype PISA_FP32 with
+ *     head_dim 64 or 128 (fp32 path); block 64 or 128.
+ *   - Every function returns a status code; pisa_last_error() gives the message of the
+ *     last failure on the calling thread.  Arguments are validated before any device
+ *     call, so argument errors are reported on a host without a GPU as well.
+ */
+#ifndef PISA_H_
+#define PISA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  PISA_OK = 0,
+  PISA_INVALID_ARG = 1,          /* null pointer, non-positive size, k outside [0, N], ... */
+  PISA_UNSUPPORTED = 2,          /* dtype / head_dim / block combination not built        */
+  PISA_WORKSPACE_TOO_SMALL = 3,
+  PISA_HIP_ERROR = 4             /* a launch failed; message carries the hipError_t name   */
+};
+
+enum { PISA_FP32 = 0, PISA_BF16 = 1 };
+
+typedef struct pisa_shape {
+  int32_t batch;      /* >= 1 */
+  int32_t heads;      /* >= 1 */
+  int32_t seq_len;    /* L >= 1 */
+  int32_t head_dim;   /* d: 64 or 128 */
+  int32_t block;      /* B: 64 or 128 (query and key/value side alike) */
+  int32_t dtype;      /* PISA_FP32 or PISA_BF16: element type of Q, K, V, O */
+  float   scale;      /* softmax scale s; <= 0 selects 1/sqrt(head_dim) */
+} pisa_shape;
+
+/* N = ceil(seq_len / block); returns -1 on non-positive arguments. */
+int32_t pisa_num_blocks(int32_t seq_len, int32_t block);
+
+/* Number k of exactly-attended blocks at sparsity r (Experiments, "Implementation
+ * Details": sparsity = share of blocks handled by the approximation):
+ * k = N - floor(r*N + 1e-9), clamped to [0, N].  Returns -1 if N < 0 or r is NaN. */
+int32_t pisa_topk_count(int32_t num_blocks, double sparsity);
+
+/* Bytes of device scratch that pisa_block_stats and pisa_select each need for this shape
+ * (the larger of: partial sums of H, reduced in a fixed order so the result is run-to-run
+ * identical; the N x N fp64 pooled logits per head).  One buffer of this size serves both
+ * calls when they run one after the other on a stream.  0 on a bad shape. */
+size_t pisa_workspace_bytes(const pisa_shape* shape);
+
+/*
+ * Alg. 1 line 1.  For every (batch, head):
+ *   qbar[i,:]  = mean of the rows of query block i            fp32 [batch,heads,N,d]
+ *   kbar[j,:]  = mean of the rows of key block j  (centroid)  fp32 [batch,heads,N,d]
+ *   vsum[j,:]  = sum  of the rows of value block j            fp32 [batch,heads,N,d]
+ *   hsum       = sum_j sum_n (k_{j,n} - kbar_j)^T v_{j,n}     fp32 [batch,heads,d,d]
+ *                (the UN-normalised sum over all N blocks of the per-block H_j of the
+ *                "Global First-Order Correction" paragraph; hsum[a][b] pairs key channel a
+ *                with value channel b)
+ *   qbar64, kbar64: the same means in fp64 [batch,heads,N,d] (block sums are accumulated
+ *                in fp64, so for bf16 inputs they are exact); pisa_select ranks with these.
+ * Outputs are written, never read.  `workspace` must hold pisa_workspace_bytes(shape).
+ */
+int32_t pisa_block_stats(const pisa_shape* shape, const void* q, const void* k, const void* v,
+                         float* qbar, float* kbar, float* vsum, float* hsum,
+                         double* qbar64, double* kbar64,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Alg. 1 line 2.  For every (batch, head, query block i): logits z_ij = s * qbar_i . kbar_j
+ * (the selection-score equation without its covariance term; softmax is monotone so the
+ * logits are ranked directly), and the k_top largest are kept; equal logits go to the lower
+ * block index.
+ *   idx      int32 [batch,heads,N,k_top], ascending and unique within a row
+ *   kth_gap  fp32  [batch,heads,N]: z of rank k_top minus z of rank k_top+1 (+inf when
+ *            k_top is 0 or N); may be NULL.  Rows with a tiny gap are the only ones where
+ *            another index set is equally valid.
+ * k_top == 0 is legal (idx may then be NULL).  N up to 4096 blocks.
+ * `workspace` must hold pisa_workspace_bytes(shape); its contents are overwritten.
+ */
+int32_t pisa_select(const pisa_shape* shape, const double* qbar64, const double* kbar64,
+                    int32_t k_top, int32_t* idx, float* kth_gap,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Alg. 1 lines 4-23 for every (batch, head, query block i), rows t of the block:
+ *   D_t = sum_{j in S_i} sum_n exp(s q_t k_{j,n}^T)  +  sum_{j in U_i} B_j exp(s q_t kbar_j^T)
+ *   N_t = sum_{j in S_i} sum_n exp(s q_t k_{j,n}^T) v_{j,n}
+ *       + sum_{j in U_i} exp(s q_t kbar_j^T) vsum_j
+ *       + (T_t / L) (s q_t) hsum ,   T_t = sum_{j in U_i} B_j exp(s q_t kbar_j^T)
+ *   out_t = N_t / D_t                         (hybrid equations; Alg. 1 lines 22-23)
+ * with S_i = idx[i, :], U_i its complement, all inside one running-max softmax.
+ *   kbar, vsum, hsum: as written by pisa_block_stats.  hsum == NULL drops the first-order
+ *            term (the zeroth-order variant of the ablation study).
+ *   idx      int32 [batch,heads,N,k_top]; must be in range, ascending and unique within a
+ *            row (as pisa_select writes it) -- contents are not checked on the device.
+ *   out      [batch,heads,seq_len,d] in shape->dtype
+ *   lse      fp32 [batch,heads,seq_len]: log D_t; may be NULL.
+ * k_top == N reproduces dense_attention; k_top == 0 is the pure approximation.
+ * N up to 4096 blocks.
+ */
+int32_t pisa_attention(const pisa_shape* shape, const void* q, const void* k, const void* v,
+                       const float* kbar, const float* vsum, const float* hsum,
+                       const int32_t* idx, int32_t k_top,
+                       void* out, float* lse, void* stream);
+
+/* Preliminaries, first equation: out = softmax(s Q K^T) V with an online softmax over
+ * 64-key tiles; lse as above (may be NULL).  shape->block only sets the tile walk. */
+int32_t dense_attention(const pisa_shape* shape, const void* q, const void* k, const void* v,
+                        void* out, float* lse, void* stream);
+
+/* Message of the last failure on this thread ("" if none).  Never NULL. */
+const char* pisa_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PISA_H_ */

@@ -1,0 +1,179 @@
+// C-ABI entry points of libpisa: argument validation and dispatch.
+// Validation runs before any device call, so bad arguments are reported on a
+// host without a GPU too.
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+
+#include "common.h"
+
+namespace pisa {
+
+static thread_local char g_err[512] = "";
+
+int32_t fail(int32_t code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+static int32_t hip_fail(const char* what, hipError_t e) {
+  return fail(PISA_HIP_ERROR, "%s: %s (%d)", what, hipGetErrorName(e), (int)e);
+}
+
+// Validates a shape and resolves it.  Returns PISA_OK or an error code.
+static int32_t resolve(const pisa_shape* s, Dims* dm) {
+  if (!s) return fail(PISA_INVALID_ARG, "shape is NULL");
+  if (s->batch < 1 || s->heads < 1 || s->seq_len < 1)
+    return fail(PISA_INVALID_ARG, "batch, heads and seq_len must be >= 1 (got %d, %d, %d)",
+                s->batch, s->heads, s->seq_len);
+  if (s->dtype != PISA_FP32 && s->dtype != PISA_BF16)
+    return fail(PISA_INVALID_ARG, "dtype must be PISA_FP32 (0) or PISA_BF16 (1), got %d", s->dtype);
+  if (s->block != 64 && s->block != 128)
+    return fail(PISA_INVALID_ARG, "block must be 64 or 128, got %d", s->block);
+  if (s->head_dim != 64 && s->head_dim != 128)
+    return fail(PISA_INVALID_ARG, "head_dim must be 64 or 128, got %d", s->head_dim);
+  if (s->dtype == PISA_BF16 && s->head_dim != 128)
+    return fail(PISA_UNSUPPORTED, "bf16 is built for head_dim 128 only (got %d)", s->head_dim);
+  if (!(s->scale == s->scale) || std::isinf(s->scale))
+    return fail(PISA_INVALID_ARG, "scale is not finite");
+  long long rows = (long long)s->batch * s->heads * s->seq_len;
+  if (rows * s->head_dim >= (1LL << 40))
+    return fail(PISA_UNSUPPORTED, "tensor too large");
+  dm->batch = s->batch;
+  dm->heads = s->heads;
+  dm->L = s->seq_len;
+  dm->d = s->head_dim;
+  dm->B = s->block;
+  dm->N = (s->seq_len + s->block - 1) / s->block;
+  dm->dtype = s->dtype;
+  dm->scale = s->scale > 0.f ? s->scale : 1.0f / std::sqrt((float)s->head_dim);
+  return PISA_OK;
+}
+
+StatsPlan stats_plan(const Dims& dm) {
+  // Aim at about 1024 workgroups over the whole launch.
+  int want = (1024 + dm.bh() - 1) / dm.bh();
+  if (want < 1) want = 1;
+  if (want > dm.N) want = dm.N;
+  StatsPlan p;
+  p.chunk_blocks = (dm.N + want - 1) / want;
+  p.n_chunks = (dm.N + p.chunk_blocks - 1) / p.chunk_blocks;
+  return p;
+}
+
+static size_t stats_workspace_bytes(const Dims& dm) {
+  StatsPlan p = stats_plan(dm);
+  return (size_t)dm.bh() * p.n_chunks * dm.d * dm.d * sizeof(float);
+}
+
+}  // namespace pisa
+
+using namespace pisa;
+
+extern "C" {
+
+int32_t pisa_num_blocks(int32_t seq_len, int32_t block) {
+  if (seq_len < 1 || block < 1) return -1;
+  return (seq_len + block - 1) / block;
+}
+
+int32_t pisa_topk_count(int32_t num_blocks, double sparsity) {
+  if (num_blocks < 0 || !(sparsity == sparsity)) return -1;
+  double approx = std::floor(sparsity * (double)num_blocks + 1e-9);
+  double k = (double)num_blocks - approx;
+  if (k < 0) k = 0;
+  if (k > num_blocks) k = num_blocks;
+  return (int32_t)k;
+}
+
+size_t pisa_workspace_bytes(const pisa_shape* shape) {
+  Dims dm;
+  if (resolve(shape, &dm) != PISA_OK) return 0;
+  return std::max(stats_workspace_bytes(dm), select_workspace_bytes(dm));
+}
+
+int32_t pisa_block_stats(const pisa_shape* shape, const void* q, const void* k, const void* v,
+                         float* qbar, float* kbar, float* vsum, float* hsum,
+                         double* qbar64, double* kbar64,
+                         void* workspace, size_t workspace_bytes, void* stream) {
+  Dims dm;
+  int32_t rc = resolve(shape, &dm);
+  if (rc != PISA_OK) return rc;
+  if (!q || !k || !v) return fail(PISA_INVALID_ARG, "q, k, v must not be NULL");
+  if (!qbar || !kbar || !vsum || !hsum || !qbar64 || !kbar64)
+    return fail(PISA_INVALID_ARG, "qbar, kbar, vsum, hsum, qbar64, kbar64 must not be NULL");
+  size_t need = stats_workspace_bytes(dm);
+  if (!workspace) return fail(PISA_INVALID_ARG, "workspace is NULL (need %zu bytes)", need);
+  if (workspace_bytes < need)
+    return fail(PISA_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, need %zu", workspace_bytes, need);
+  hipError_t e = launch_block_stats(dm, q, k, v, qbar, kbar, vsum, hsum, qbar64, kbar64,
+                                    (float*)workspace, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail("pisa_block_stats", e);
+  return PISA_OK;
+}
+
+int32_t pisa_select(const pisa_shape* shape, const double* qbar64, const double* kbar64,
+                    int32_t k_top, int32_t* idx, float* kth_gap,
+                    void* workspace, size_t workspace_bytes, void* stream) {
+  Dims dm;
+  int32_t rc = resolve(shape, &dm);
+  if (rc != PISA_OK) return rc;
+  if (!qbar64 || !kbar64) return fail(PISA_INVALID_ARG, "qbar64 and kbar64 must not be NULL");
+  if (k_top < 0 || k_top > dm.N)
+    return fail(PISA_INVALID_ARG, "k_top = %d outside [0, N = %d]", k_top, dm.N);
+  if (k_top > 0 && !idx) return fail(PISA_INVALID_ARG, "idx is NULL but k_top > 0");
+  if (dm.N > kMaxBlocks)
+    return fail(PISA_UNSUPPORTED, "at most %d blocks are supported (N = %d)", kMaxBlocks, dm.N);
+  size_t need = select_workspace_bytes(dm);
+  if (!workspace) return fail(PISA_INVALID_ARG, "workspace is NULL (need %zu bytes)", need);
+  if (workspace_bytes < need)
+    return fail(PISA_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, need %zu", workspace_bytes, need);
+  hipError_t e = launch_select(dm, qbar64, kbar64, k_top, idx, kth_gap, (double*)workspace,
+                               (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail("pisa_select", e);
+  return PISA_OK;
+}
+
+static int32_t run_attention(const Dims& dm, const AttnArgs& a, void* stream, const char* who) {
+  hipError_t e = dm.dtype == PISA_BF16 ? launch_attention_bf16(dm, a, (hipStream_t)stream)
+                                       : launch_attention_fp32(dm, a, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(who, e);
+  return PISA_OK;
+}
+
+int32_t pisa_attention(const pisa_shape* shape, const void* q, const void* k, const void* v,
+                       const float* kbar, const float* vsum, const float* hsum,
+                       const int32_t* idx, int32_t k_top,
+                       void* out, float* lse, void* stream) {
+  Dims dm;
+  int32_t rc = resolve(shape, &dm);
+  if (rc != PISA_OK) return rc;
+  if (!q || !k || !v || !out) return fail(PISA_INVALID_ARG, "q, k, v, out must not be NULL");
+  if (k_top < 0 || k_top > dm.N)
+    return fail(PISA_INVALID_ARG, "k_top = %d outside [0, N = %d]", k_top, dm.N);
+  if (k_top > 0 && !idx) return fail(PISA_INVALID_ARG, "idx is NULL but k_top > 0");
+  if (k_top < dm.N && (!kbar || !vsum))
+    return fail(PISA_INVALID_ARG, "kbar and vsum must not be NULL when k_top < N");
+  if (dm.N > kMaxBlocks)
+    return fail(PISA_UNSUPPORTED, "at most %d blocks are supported (N = %d)", kMaxBlocks, dm.N);
+  AttnArgs a{q, k, v, kbar, vsum, hsum, idx, k_top, out, lse, false};
+  return run_attention(dm, a, stream, "pisa_attention");
+}
+
+int32_t dense_attention(const pisa_shape* shape, const void* q, const void* k, const void* v,
+                        void* out, float* lse, void* stream) {
+  Dims dm;
+  int32_t rc = resolve(shape, &dm);
+  if (rc != PISA_OK) return rc;
+  if (!q || !k || !v || !out) return fail(PISA_INVALID_ARG, "q, k, v, out must not be NULL");
+  AttnArgs a{q, k, v, nullptr, nullptr, nullptr, nullptr, dm.N, out, lse, true};
+  return run_attention(dm, a, stream, "dense_attention");
+}
+
+const char* pisa_last_error(void) { return pisa::g_err; }
+
+}  // extern "C"

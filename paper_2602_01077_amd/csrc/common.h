@@ -1,0 +1,64 @@
+// Internal declarations shared by the translation units of libpisa.
+// Host-side only: problem dimensions, error reporting, launcher prototypes.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "pisa.h"
+
+namespace pisa {
+
+// Resolved problem dimensions (shape after validation).
+struct Dims {
+  int batch, heads, L, d, B, N;   // N = ceil(L / B)
+  int dtype;                      // PISA_FP32 / PISA_BF16
+  float scale;                    // resolved softmax scale
+  int bh() const { return batch * heads; }
+};
+
+// Key/value tiles are always 64 rows; a block of 128 tokens is walked as two tiles.
+constexpr int kTile = 64;
+// Largest block count the selection and the Phase-2 column mask are sized for.
+constexpr int kMaxBlocks = 4096;
+
+// Records the message returned by pisa_last_error() and returns `code`.
+int32_t fail(int32_t code, const char* fmt, ...);
+
+// Chunking of the block axis used by the statistics kernels: each workgroup
+// accumulates H over `chunk_blocks` consecutive blocks of one head, and the
+// partial sums are reduced in chunk order afterwards.
+struct StatsPlan {
+  int chunk_blocks;
+  int n_chunks;
+};
+StatsPlan stats_plan(const Dims& dm);
+
+// Launchers (each returns hipGetLastError() after its launches).
+hipError_t launch_block_stats(const Dims& dm, const void* q, const void* k, const void* v,
+                              float* qbar, float* kbar, float* vsum, float* hsum,
+                              double* qbar64, double* kbar64, float* partial_h,
+                              hipStream_t stream);
+size_t select_workspace_bytes(const Dims& dm);
+hipError_t launch_select(const Dims& dm, const double* qbar64, const double* kbar64, int k_top,
+                         int32_t* idx, float* kth_gap, double* zbuf, hipStream_t stream);
+
+// Arguments of the attention kernels (dense and PISA share them).
+struct AttnArgs {
+  const void* q;
+  const void* k;
+  const void* v;
+  const float* kbar;     // null for dense
+  const float* vsum;     // null for dense
+  const float* hsum;     // null: no first-order term
+  const int32_t* idx;    // null for dense
+  int k_top;
+  void* out;
+  float* lse;            // may be null
+  bool dense;
+};
+hipError_t launch_attention_fp32(const Dims& dm, const AttnArgs& a, hipStream_t stream);
+hipError_t launch_attention_bf16(const Dims& dm, const AttnArgs& a, hipStream_t stream);
+
+}  // namespace pisa

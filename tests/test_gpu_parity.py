@@ -1,0 +1,276 @@
+"""GPU parity: every stage of libpisa, called through the C ABI, against the fp64 CPU
+oracle on the same seeded inputs.
+
+Bars (benchmark spec): index sets bit-exact except where the oracle's k-th gap is
+below 1e-6 (reported); outputs within 1e-4 (fp32) / 2e-2 with per-row cosine >= 0.999
+(bf16), relative error taken per row against the row's largest reference magnitude.
+Statistics: means and sums to fp32 rounding, fp64 means to 1e-12, hsum to 1e-4 of its
+largest entry.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import pisa_oracle as po
+from workloads import WORKLOADS, make_qkv
+from parity_util import (COS_MIN, GAP_TOL, TOL, check_index_rows_valid, compare_index_rows, head_np,
+                         row_errors, rows_of_blocks)
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def oracle_head(q, k, v, h, block, scale, k_top, per_block_H=False):
+    Q, K, V = head_np(q, 0, h), head_np(k, 0, h), head_np(v, 0, h)
+    st = po.block_stats(Q, K, V, block, per_block_H=per_block_H)
+    idx, gap = po.select(st["qbar"], st["kbar"], scale, k_top)
+    return Q, K, V, st, idx, gap
+
+
+def check_stats(stats_gpu, st, h, dtype):
+    for name in ("qbar", "kbar", "vsum"):
+        got = head_np(stats_gpu[name], 0, h)
+        ref = st[name]
+        assert np.abs(got - ref).max() <= 1e-6 * max(1.0, np.abs(ref).max()), name
+    for name in ("qbar64", "kbar64"):
+        got = head_np(stats_gpu[name], 0, h)
+        assert np.abs(got - st[name[:-2]]).max() <= 1e-12, name
+    got = head_np(stats_gpu["hsum"], 0, h)
+    assert np.abs(got - st["hsum"]).max() <= 1e-4 * np.abs(st["hsum"]).max(), "hsum"
+
+
+def check_select(idx_gpu, gap_gpu, idx_ref, gap_ref, N, where=""):
+    check_index_rows_valid(idx_gpu, N)
+    hard, soft = compare_index_rows(idx_gpu, idx_ref, gap_ref)
+    if len(soft):
+        print(f"[select]{where} rows differing at oracle gap < {GAP_TOL}: {soft.tolist()}")
+    assert len(hard) == 0, f"{where} index rows differ at gaps >= {GAP_TOL}: {hard.tolist()[:10]}"
+    if gap_gpu is not None and idx_ref.shape[1] not in (0, N):
+        assert np.abs(gap_gpu - gap_ref).max() <= 1e-5 * max(1.0, np.abs(gap_ref).max())
+    return soft
+
+
+def run_full_case(pisa, w, blocks_per_head=None, heads=None, first_order=True, seed_rows=0):
+    """Runs stats -> select -> attention and dense on the GPU and checks each stage of
+    the listed heads against the oracle (all query blocks unless blocks_per_head)."""
+    q, k, v = make_qkv(w, device="cpu")
+    qd, kd, vd = q.to(DEV), k.to(DEV), v.to(DEV)
+    res = pisa.pisa_forward(qd, kd, vd, w.block, w.sparsity, first_order=first_order, want_lse=True)
+    dense, dense_lse = pisa.dense_attention(qd, kd, vd, w.block, want_lse=True)
+    torch.cuda.synchronize()
+    scale = pisa.resolved_scale(w.head_dim)
+    N, k_top = w.num_blocks, res["k_top"]
+    assert k_top == w.topk
+    tol = TOL[q.dtype]
+    mode = "hybrid" if first_order else "pisa0"
+    worst = dict(pisa=0.0, dense=0.0, cos=1.0)
+    for h in (range(w.heads) if heads is None else heads):
+        Q, K, V, st, idx_ref, gap_ref = oracle_head(q, k, v, h, w.block, scale, k_top)
+        check_stats(res["stats"], st, h, q.dtype)
+        idx_gpu = res["idx"][0, h].cpu().numpy()
+        gap_gpu = res["kth_gap"][0, h].cpu().numpy().astype(np.float64)
+        check_select(idx_gpu, gap_gpu, idx_ref, gap_ref, N, where=f" {w.name} head {h}")
+        blocks = list(range(N)) if blocks_per_head is None else blocks_per_head
+        rows = rows_of_blocks(blocks, w.block, w.seq_len)
+        # the attention stage is judged on the index sets it was given
+        ref, ref_lse = po.attention_head(Q, K, V, w.block, idx_gpu, scale, mode, blocks=blocks, stats=st)
+        got = res["out"][0, h].float().cpu().numpy()[rows]
+        rel, cos = row_errors(got, ref)
+        assert rel <= tol and cos >= COS_MIN, (w.name, h, rel, cos)
+        lse = res["lse"][0, h].cpu().numpy()[rows]
+        assert np.abs(lse - ref_lse).max() <= (1e-4 if q.dtype == torch.float32 else 2e-2)
+        dref, dref_lse = po.attention_head(Q, K, V, w.block, None, scale, "dense", blocks=blocks)
+        dgot = dense[0, h].float().cpu().numpy()[rows]
+        drel, dcos = row_errors(dgot, dref)
+        assert drel <= tol and dcos >= COS_MIN, (w.name, h, "dense", drel, dcos)
+        assert np.abs(dense_lse[0, h].cpu().numpy()[rows] - dref_lse).max() <= (1e-4 if q.dtype == torch.float32 else 2e-2)
+        worst["pisa"] = max(worst["pisa"], rel)
+        worst["dense"] = max(worst["dense"], drel)
+        worst["cos"] = min(worst["cos"], cos, dcos)
+    print(f"[parity] {w.name} L={w.seq_len} B={w.block} r={w.sparsity} k={k_top}: "
+          f"pisa {worst['pisa']:.2e} dense {worst['dense']:.2e} cos_min {worst['cos']:.6f}")
+    return res
+
+
+def test_tiny_config_full(lib):
+    """Config 'tiny' (fp32, d=64, 16x16 blocks, r=0.75) compared in full."""
+    res = run_full_case(lib, WORKLOADS["tiny"])
+    assert res["idx"].shape == (1, 2, 16, 4)
+
+
+@pytest.mark.parametrize("L,H,d,B,r", [
+    (1000, 2, 64, 64, 0.75),     # ragged last block (40 rows)
+    (600, 1, 128, 128, 0.5),     # block 128, last block 88 rows
+    (777, 2, 128, 64, 0.9),
+    (520, 1, 64, 128, 0.7),      # block 128 whose second tile is all padding
+    (300, 1, 64, 64, 1.0),       # k = 0: pure approximation
+    (300, 2, 64, 64, 0.0),       # k = N: everything exact
+    (64, 1, 64, 64, 0.5),        # a single block
+    (1, 1, 64, 64, 0.0),         # a single token
+])
+def test_fp32_cases(lib, L, H, d, B, r):
+    w = WORKLOADS["tiny"].with_(name=f"fp32-{L}", heads=H, seq_len=L, head_dim=d, block=B, sparsity=r, seed=10 + L)
+    run_full_case(lib, w)
+
+
+@pytest.mark.parametrize("L,H,B,r", [
+    (1000, 3, 64, 0.8),
+    (2000, 2, 128, 0.85),        # block 128, last block 80 rows
+    (1930, 2, 128, 0.6),         # block 128, last block 10 rows: its second tile is all padding
+    (70, 1, 64, 0.5),            # two blocks, the second with 6 rows
+    (64, 1, 64, 0.0),
+    (37, 1, 64, 0.0),            # shorter than a block
+    (640, 2, 64, 1.0),           # k = 0
+    (4200, 2, 64, 0.95),         # several Phase-2 tiles and a ragged centroid tile
+])
+def test_bf16_cases(lib, L, H, B, r):
+    w = WORKLOADS["flux"].with_(name=f"bf16-{L}", heads=H, seq_len=L, block=B, sparsity=r, seed=20 + L,
+                                grid=None, block_offset_std=0.5)
+    run_full_case(lib, w)
+
+
+def test_bf16_zeroth_order_only(lib):
+    """hsum = NULL drops the global first-order term (zeroth-order variant)."""
+    w = WORKLOADS["flux"].with_(name="bf16-0th", heads=2, seq_len=1500, sparsity=0.8, grid=None,
+                                block_offset_std=0.5)
+    run_full_case(lib, w, first_order=False)
+
+
+@pytest.mark.parametrize("dtype,d,B", [("bf16", 128, 64), ("bf16", 128, 128), ("fp32", 64, 64), ("fp32", 128, 128)])
+def test_all_blocks_selected_is_bitwise_dense(lib, dtype, d, B):
+    """At r = 0 the PISA kernel must return exactly what the dense kernel returns."""
+    w = WORKLOADS["tiny"].with_(name="r0", heads=2, seq_len=1100, head_dim=d, dtype=dtype, block=B, sparsity=0.0)
+    q, k, v = (x.to(DEV) for x in make_qkv(w))
+    res = lib.pisa_forward(q, k, v, B, 0.0, want_lse=True)
+    dense, lse = lib.dense_attention(q, k, v, B, want_lse=True)
+    torch.cuda.synchronize()
+    assert res["k_top"] == w.num_blocks
+    assert torch.equal(res["out"], dense)
+    assert torch.equal(res["lse"], lse)
+
+
+def test_flux_config_full(lib):
+    """FLUX.1-dev-shaped config (24 heads, N=4608, bf16, r=0.85) compared in full."""
+    run_full_case(lib, WORKLOADS["flux"])
+
+
+def test_stats_are_run_to_run_identical(lib):
+    """hsum is reduced in a fixed order: two runs must agree bit for bit."""
+    w = WORKLOADS["flux"].with_(heads=3, seq_len=3000, grid=None)
+    q, k, v = (x.to(DEV) for x in make_qkv(w))
+    a = lib.block_stats(q, k, v, 64)
+    b = lib.block_stats(q, k, v, 64)
+    torch.cuda.synchronize()
+    for name in a:
+        assert torch.equal(a[name], b[name]), name
+
+
+def test_select_ties_and_duplicates(lib):
+    """Duplicate centroids give exactly equal logits: the lower index must win, and
+    the reported gap is zero there."""
+    N, d, H = 40, 64, 2
+    rng = np.random.default_rng(0)
+    qb = rng.standard_normal((1, H, N, d))
+    kb = rng.standard_normal((1, H, N, d))
+    kb[0, :, 7] = kb[0, :, 3]
+    kb[0, :, 21] = kb[0, :, 3]
+    kb[0, 1, 30:] = kb[0, 1, 29]
+    shape = lib.PisaShape(1, H, N * 64, d, 64, lib.PISA_FP32, 0.0)
+    scale = lib.resolved_scale(d)
+    for k_top in (1, 2, 5, 17, 39):
+        idx, gap = lib.select(shape, torch.from_numpy(qb).to(DEV), torch.from_numpy(kb).to(DEV), k_top)
+        torch.cuda.synchronize()
+        for h in range(H):
+            ref, gref = po.select(qb[0, h], kb[0, h], scale, k_top)
+            # duplicates make exact ties, so the comparison must be exact there too
+            z = po.pooled_logits(qb[0, h], kb[0, h], scale)
+            got = idx[0, h].cpu().numpy()
+            check_index_rows_valid(got, N)
+            for i in range(N):
+                if not np.array_equal(got[i], ref[i]):
+                    # only legal if the sets carry the same logit multiset (fp64 rounding of z itself)
+                    assert np.allclose(np.sort(z[i, got[i]]), np.sort(z[i, ref[i]]), atol=1e-12), (k_top, h, i)
+            assert np.abs(gap[0, h].cpu().numpy() - gref).max() < 1e-5
+
+
+def _sampled_blocks(w, rng, extra=()):
+    N = w.num_blocks
+    fixed = {0, N - 1, *extra}
+    rand = set(rng.choice(N, size=14, replace=False).tolist())
+    return sorted(fixed | rand)
+
+
+@pytest.mark.parametrize("name", ["wan", "hunyuan"])
+def test_video_configs_sampled(lib, name):
+    """Wan2.1-14B- and Hunyuan-Video-shaped configs at full size in the launch
+    configuration the bench times.  Statistics and index sets are compared for every
+    head in full; outputs on sampled query blocks (first, ragged last, the video/text
+    straddling block, 14 random) of 8 heads."""
+    w = WORKLOADS[name]
+    scale = lib.resolved_scale(w.head_dim)
+    q, k, v = make_qkv(w, device=DEV)
+    res = lib.pisa_forward(q, k, v, w.block, w.sparsity, want_lse=True)
+    dense, _ = lib.dense_attention(q, k, v, w.block)
+    torch.cuda.synchronize()
+    N, k_top = w.num_blocks, w.topk
+    rng = np.random.default_rng(99)
+    out_heads = set(rng.choice(w.heads, size=8, replace=False).tolist())
+    n_grid = int(np.prod(w.grid))
+    straddle = [n_grid // w.block] if n_grid < w.seq_len else []
+    soft_total, worst, worst_d, cos_min = 0, 0.0, 0.0, 1.0
+    for h in range(w.heads):
+        Q, K, V, st, idx_ref, gap_ref = oracle_head(q, k, v, h, w.block, scale, k_top)
+        check_stats(res["stats"], st, h, q.dtype)
+        idx_gpu = res["idx"][0, h].cpu().numpy()
+        gap_gpu = res["kth_gap"][0, h].cpu().numpy().astype(np.float64)
+        soft_total += len(check_select(idx_gpu, gap_gpu, idx_ref, gap_ref, N, where=f" {name} head {h}"))
+        if h in out_heads:
+            blocks = _sampled_blocks(w, rng, straddle)
+            rows = rows_of_blocks(blocks, w.block, w.seq_len)
+            ref, _ = po.attention_head(Q, K, V, w.block, idx_gpu, scale, "hybrid", blocks=blocks, stats=st)
+            rel, cos = row_errors(res["out"][0, h].float().cpu().numpy()[rows], ref)
+            dref, _ = po.attention_head(Q, K, V, w.block, None, scale, "dense", blocks=blocks)
+            drel, dcos = row_errors(dense[0, h].float().cpu().numpy()[rows], dref)
+            assert rel <= TOL[q.dtype] and cos >= COS_MIN, (name, h, rel, cos)
+            assert drel <= TOL[q.dtype] and dcos >= COS_MIN, (name, h, "dense", drel, dcos)
+            worst, worst_d, cos_min = max(worst, rel), max(worst_d, drel), min(cos_min, cos, dcos)
+        print(f"[{name}] head {h} done", flush=True)
+    print(f"[parity] {name}: pisa {worst:.2e} dense {worst_d:.2e} cos_min {cos_min:.6f} "
+          f"index rows differing at tiny gaps: {soft_total}")
+
+
+@pytest.mark.parametrize("block,r", [(64, 0.0), (64, 0.5), (64, 0.75), (64, 0.95), (128, 0.85)])
+def test_wan_sweep_sampled(lib, block, r):
+    """Sparsity / block-size sweep at the Wan shape (r = 0.85, block 64 is the test above).
+    8 heads at full length; sampled query blocks against the oracle; r = 0 equals dense."""
+    w = WORKLOADS["wan"].with_(block=block, sparsity=r)
+    heads = [0, 7, 13, 19, 22, 28, 33, 39]
+    scale = lib.resolved_scale(w.head_dim)
+    q, k, v = make_qkv(w, device=DEV, heads=heads)
+    res = lib.pisa_forward(q, k, v, block, r)
+    torch.cuda.synchronize()
+    N, k_top = w.num_blocks, w.topk
+    assert res["k_top"] == k_top
+    if r == 0.0:
+        dense, _ = lib.dense_attention(q, k, v, block)
+        torch.cuda.synchronize()
+        assert torch.equal(res["out"], dense)
+    rng = np.random.default_rng(5)
+    worst, cos_min = 0.0, 1.0
+    for slot in range(len(heads)):
+        Q, K, V, st, idx_ref, gap_ref = oracle_head(q, k, v, slot, block, scale, k_top)
+        check_stats(res["stats"], st, slot, q.dtype)
+        idx_gpu = res["idx"][0, slot].cpu().numpy()
+        check_select(idx_gpu, res["kth_gap"][0, slot].cpu().numpy().astype(np.float64), idx_ref, gap_ref, N,
+                     where=f" wan B={block} r={r} head {heads[slot]}")
+        blocks = _sampled_blocks(w, rng)[:: 2 if r == 0.0 else 1]
+        if N - 1 not in blocks:
+            blocks.append(N - 1)
+        rows = rows_of_blocks(blocks, block, w.seq_len)
+        ref, _ = po.attention_head(Q, K, V, block, idx_gpu, scale, "hybrid", blocks=blocks, stats=st)
+        rel, cos = row_errors(res["out"][0, slot].float().cpu().numpy()[rows], ref)
+        assert rel <= TOL[q.dtype] and cos >= COS_MIN, (block, r, heads[slot], rel, cos)
+        worst, cos_min = max(worst, rel), min(cos_min, cos)
+    print(f"[parity] wan B={block} r={r} k={k_top}: pisa {worst:.2e} cos_min {cos_min:.6f}")
