@@ -1,0 +1,195 @@
+#!/usr/bin/env python3
+"""Benchmark of the PISA hot path on one MI355X.
+
+A "step" is one pass of the whole hot path -- pisa_block_stats, pisa_select,
+pisa_attention -- over one batch of seeded synthetic Q/K/V already resident in HBM.
+Default workload: the Wan2.1-14B-shaped layer (B=1, H=40, N=75600, d=128, bf16,
+block 64, sparsity 0.85), the configuration the headline metric is quoted on.
+
+Prints ONE JSON line.  `value` is ms per call of the whole hot path (lower is
+better); per-stage times, the library's own dense_attention time and the speed-up
+over it ride along.  `roofline` covers the dominant kernel (the fused attention
+kernel, MFMA-bound); `cpu_baseline` is the fp64 CPU oracle timed on a bounded sample
+of the same workload on this host and scaled to a full call.
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def attention_flops(L, d, H, B, k_top, N):
+    """Algorithmic flops of one pisa_attention call: exact tiles + centroid tiles
+    (QK^T and PV each 2*rows*cols*d) + the d x d first-order product."""
+    return 4.0 * L * d * H * (k_top * B + N) + 2.0 * L * d * d * H
+
+
+def dense_flops(L, d, H):
+    return 4.0 * L * L * d * H
+
+
+def cpu_baseline(w, q, k, v, scale, k_top, budget_blocks=24):
+    """Times the oracle on head 0: full statistics, full selection, and the attention
+    rows of `budget_blocks` query blocks; scales to all blocks and heads."""
+    import numpy as np
+    from oracle import pisa_oracle as po
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    Q, K, V = (x[0, 0].to("cpu").double().numpy() for x in (q, k, v))
+    t0 = time.perf_counter()
+    st = po.block_stats(Q, K, V, w.block)
+    t1 = time.perf_counter()
+    idx, _ = po.select(st["qbar"], st["kbar"], scale, k_top)
+    t2 = time.perf_counter()
+    N = w.num_blocks
+    blocks = sorted(set(np.linspace(0, N - 1, budget_blocks).astype(int).tolist()))
+    po.attention_head(Q, K, V, w.block, idx, scale, "hybrid", blocks=blocks, stats=st)
+    t3 = time.perf_counter()
+    per_head = (t1 - t0) + (t2 - t1) + (t3 - t2) / len(blocks) * N
+    total_ms = per_head * w.heads * w.batch * 1e3
+    return {
+        "value": round(total_ms, 1), "unit": "ms/call", "cores": int(cores), "kind": "oracle",
+        "sample": (f"head 0 of {w.heads}: full block statistics ({t1 - t0:.2f} s) and selection "
+                   f"({t2 - t1:.2f} s), attention rows of {len(blocks)} of {N} query blocks "
+                   f"({t3 - t2:.2f} s); extrapolated to all query blocks and heads"),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="wan", choices=["tiny", "flux", "wan", "hunyuan"])
+    ap.add_argument("--sparsity", type=float, default=None)
+    ap.add_argument("--block", type=int, default=None)
+    ap.add_argument("--dense-steps", type=int, default=3, help="timed dense_attention calls (0 = skip)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--traffic-json", default=None,
+                    help="file with {'fetch_bytes':..,'write_bytes':..} per attention launch from rocprofv3 --pmc")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path shards over heads without "
+              "communication; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2602_01077_amd as pisa
+    from workloads import WORKLOADS, make_qkv
+
+    w = WORKLOADS[args.workload]
+    if args.sparsity is not None:
+        w = w.with_(sparsity=args.sparsity)
+    if args.block is not None:
+        w = w.with_(block=args.block)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    q, k, v = make_qkv(w, device=dev)
+    N, k_top = w.num_blocks, w.topk
+    scale = pisa.resolved_scale(w.head_dim)
+    shape = pisa.make_shape(q, w.block)
+    ws = pisa.alloc_workspace(shape, dev)
+    b, h, L, d = q.shape
+    f32, f64 = torch.float32, torch.float64
+    stats = dict(qbar=torch.empty(b, h, N, d, dtype=f32, device=dev),
+                 kbar=torch.empty(b, h, N, d, dtype=f32, device=dev),
+                 vsum=torch.empty(b, h, N, d, dtype=f32, device=dev),
+                 hsum=torch.empty(b, h, d, d, dtype=f32, device=dev),
+                 qbar64=torch.empty(b, h, N, d, dtype=f64, device=dev),
+                 kbar64=torch.empty(b, h, N, d, dtype=f64, device=dev))
+    idx = torch.empty(b, h, N, k_top, dtype=torch.int32, device=dev)
+    gap = torch.empty(b, h, N, dtype=f32, device=dev)
+    out = torch.empty_like(q)
+
+    def step(events=None):
+        if events:
+            events[0].record()
+        pisa.block_stats_into(shape, q, k, v, stats, ws)
+        if events:
+            events[1].record()
+        pisa.select_into(shape, stats["qbar64"], stats["kbar64"], k_top, idx, gap, ws)
+        if events:
+            events[2].record()
+        pisa.attention(shape, q, k, v, stats["kbar"], stats["vsum"], stats["hsum"], idx, k_top, out=out)
+        if events:
+            events[3].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(evs[s])
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    stage = [sum(e[i].elapsed_time(e[i + 1]) for e in evs) / args.steps for i in range(3)]
+
+    dense_ms = None
+    if args.dense_steps > 0:
+        dout = torch.empty_like(q)
+        pisa.dense_attention(q, k, v, w.block, out=dout)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.dense_steps):
+            pisa.dense_attention(q, k, v, w.block, out=dout)
+        e1.record()
+        torch.cuda.synchronize()
+        dense_ms = e0.elapsed_time(e1) / args.dense_steps
+        num = (out.float() - dout.float()).abs().sum().item()
+        den = dout.float().abs().sum().item()
+        l1_vs_dense = num / den
+    else:
+        l1_vs_dense = None
+
+    fl_attn = attention_flops(L, d, h * b, w.block, k_top, N)
+    fl_dense = dense_flops(L, d, h * b)
+    attn_ms = stage[2]
+    achieved = fl_attn / (attn_ms * 1e-3) / 1e12
+    traffic = None
+    if args.traffic_json and os.path.exists(args.traffic_json):
+        with open(args.traffic_json) as f:
+            traffic = json.load(f)
+    in_bytes = 3 * q.numel() * q.element_size()
+    result = {
+        "metric": "PISA attn ms/call & MFMA util at Wan2.1 shape, r=0.85; speedup vs dense",
+        "value": round(wall_ms, 4), "unit": "ms/call", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(wall_ms, 4), "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name}: B={b} H={h} N={L} d={d} {w.dtype} block={w.block} "
+                               f"sparsity={w.sparsity} (k={k_top} of {N} blocks exact)",
+                   "seed": w.seed},
+        "stages_ms": {"pisa_block_stats": round(stage[0], 4), "pisa_select": round(stage[1], 4),
+                      "pisa_attention": round(stage[2], 4)},
+        "stats_hbm_GBps": round(in_bytes / (stage[0] * 1e-3) / 1e9, 1),
+        "attention_algorithmic_TFLOPs": round(achieved, 1),
+        "dense_equivalent_TFLOPs": round(fl_dense / (wall_ms * 1e-3) / 1e12, 1),
+        "dense_attention_ms": None if dense_ms is None else round(dense_ms, 3),
+        "dense_attention_TFLOPs": None if dense_ms is None else round(fl_dense / (dense_ms * 1e-3) / 1e12, 1),
+        "speedup_vs_dense": None if dense_ms is None else round(dense_ms / wall_ms, 3),
+        "speedup_vs_dense_attention_only": None if dense_ms is None else round(dense_ms / attn_ms, 3),
+        "l1_error_vs_dense": None if l1_vs_dense is None else round(l1_vs_dense, 6),
+        "roofline": {"kernel": "attn_bf16_kernel (pisa_attention)", "bound": "mfma",
+                     "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": traffic},
+    }
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(w, q, k, v, scale, k_top)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()
