@@ -67,6 +67,10 @@ def cpu_baseline(w, q, k, v, scale, k_top, budget_blocks=24):
     }
 
 
+def note(msg):
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -77,6 +81,8 @@ def main():
     ap.add_argument("--block", type=int, default=None)
     ap.add_argument("--dense-steps", type=int, default=3, help="timed dense_attention calls (0 = skip)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--copy-calibration", type=int, default=0,
+                    help="also run this many plain device copies of 1 GiB (reference for rocprofv3 --pmc byte counters)")
     ap.add_argument("--traffic-json", default=None,
                     help="file with {'fetch_bytes':..,'write_bytes':..} per attention launch from rocprofv3 --pmc")
     args = ap.parse_args()
@@ -97,6 +103,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     q, k, v = make_qkv(w, device=dev)
+    torch.cuda.synchronize()
+    note(f"inputs ready: {w.name} {tuple(q.shape)} {w.dtype}")
     N, k_top = w.num_blocks, w.topk
     scale = pisa.resolved_scale(w.head_dim)
     shape = pisa.make_shape(q, w.block)
@@ -135,6 +143,7 @@ def main():
         step(evs[s])
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    note(f"{args.steps} timed steps done: {wall_ms:.3f} ms/step")
     stage = [sum(e[i].elapsed_time(e[i + 1]) for e in evs) / args.steps for i in range(3)]
 
     dense_ms = None
@@ -152,8 +161,18 @@ def main():
         num = (out.float() - dout.float()).abs().sum().item()
         den = dout.float().abs().sum().item()
         l1_vs_dense = num / den
+        note(f"dense_attention: {dense_ms:.3f} ms")
     else:
         l1_vs_dense = None
+
+    if args.copy_calibration > 0:
+        # int32 add-one over 1 GiB: an elementwise kernel that reads 1 GiB and writes 1 GiB
+        src = torch.ones(1 << 28, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(args.copy_calibration):
+            torch.add(src, 1, out=dst)
+        torch.cuda.synchronize()
+        note("copy calibration done")
 
     fl_attn = attention_flops(L, d, h * b, w.block, k_top, N)
     fl_dense = dense_flops(L, d, h * b)
