@@ -130,7 +130,8 @@ def main():
         pisa.select_into(shape, stats["qbar64"], stats["kbar64"], k_top, idx, gap, ws)
         if events:
             events[2].record()
-        pisa.attention(shape, q, k, v, stats["kbar"], stats["vsum"], stats["hsum"], idx, k_top, out=out)
+        pisa.attention(shape, q, k, v, stats["kbar"], stats["vsum"], stats["hsum"], idx, k_top, out=out,
+                       workspace=ws)
         if events:
             events[3].record()
 

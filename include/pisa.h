@@ -62,10 +62,11 @@ int32_t pisa_num_blocks(int32_t seq_len, int32_t block);
  * k = N - floor(r*N + 1e-9), clamped to [0, N].  Returns -1 if N < 0 or r is NaN. */
 int32_t pisa_topk_count(int32_t num_blocks, double sparsity);
 
-/* Bytes of device scratch that pisa_block_stats and pisa_select each need for this shape
- * (the larger of: partial sums of H, reduced in a fixed order so the result is run-to-run
- * identical; the N x N fp64 pooled logits per head).  One buffer of this size serves both
- * calls when they run one after the other on a stream.  0 on a bad shape. */
+/* Bytes of device scratch that pisa_block_stats, pisa_select and pisa_attention each need
+ * for this shape (the largest of: partial sums of H, reduced in a fixed order so the result
+ * is run-to-run identical; the N x N fp64 pooled logits per head; the bf16 centroid tiles
+ * and the packed hsum the attention kernel streams).  One buffer of this size serves all
+ * three calls when they run one after the other on a stream.  0 on a bad shape. */
 size_t pisa_workspace_bytes(const pisa_shape* shape);
 
 /*
@@ -117,12 +118,14 @@ int32_t pisa_select(const pisa_shape* shape, const double* qbar64, const double*
  *   out      [batch,heads,seq_len,d] in shape->dtype
  *   lse      fp32 [batch,heads,seq_len]: log D_t; may be NULL.
  * k_top == N reproduces dense_attention; k_top == 0 is the pure approximation.
- * N up to 4096 blocks.
+ * N up to 4096 blocks.  `workspace` must hold pisa_workspace_bytes(shape) when k_top < N
+ * (it may be NULL when k_top == N); its contents are overwritten.
  */
 int32_t pisa_attention(const pisa_shape* shape, const void* q, const void* k, const void* v,
                        const float* kbar, const float* vsum, const float* hsum,
                        const int32_t* idx, int32_t k_top,
-                       void* out, float* lse, void* stream);
+                       void* out, float* lse,
+                       void* workspace, size_t workspace_bytes, void* stream);
 
 /* Preliminaries, first equation: out = softmax(s Q K^T) V with an online softmax over
  * 64-key tiles; lse as above (may be NULL).  shape->block only sets the tile walk. */

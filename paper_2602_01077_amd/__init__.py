@@ -55,7 +55,7 @@ def _load() -> ctypes.CDLL:
     lib.pisa_block_stats.restype = i32
     lib.pisa_select.argtypes = [shp, vp, vp, i32, vp, vp, vp, sz, vp]
     lib.pisa_select.restype = i32
-    lib.pisa_attention.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp]
+    lib.pisa_attention.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
     lib.pisa_attention.restype = i32
     lib.dense_attention.argtypes = [shp, vp, vp, vp, vp, vp, vp]
     lib.dense_attention.restype = i32
@@ -185,8 +185,10 @@ def select_into(shape, qbar64, kbar64, k_top: int, idx, gap, workspace) -> None:
 
 def attention(shape: PisaShape, q, k, v, kbar, vsum, hsum, idx, k_top: int,
               out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None,
-              want_lse: bool = False):
+              want_lse: bool = False, workspace: Optional[torch.Tensor] = None):
     """pisa_attention.  Returns (out, lse or None)."""
+    if workspace is None:
+        workspace = alloc_workspace(shape, q.device)
     if out is None:
         out = torch.empty_like(q)
     if lse is None and want_lse:
@@ -196,7 +198,8 @@ def attention(shape: PisaShape, q, k, v, kbar, vsum, hsum, idx, k_top: int,
         _dev(kbar, "kbar", torch.float32), _dev(vsum, "vsum", torch.float32),
         _dev(hsum, "hsum", torch.float32),
         _dev(idx, "idx", torch.int32) if k_top > 0 else None, k_top,
-        _dev(out, "out", like=q), _dev(lse, "lse", torch.float32), _stream()))
+        _dev(out, "out", like=q), _dev(lse, "lse", torch.float32),
+        _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream()))
     return out, lse
 
 
@@ -228,5 +231,6 @@ def pisa_forward(q, k, v, block: int = 64, sparsity: float = 0.85, first_order: 
     stats = block_stats(q, k, v, block, ws)
     idx, gap = select(shape, stats["qbar64"], stats["kbar64"], k_top, ws)
     out, lse = attention(shape, q, k, v, stats["kbar"], stats["vsum"],
-                         stats["hsum"] if first_order else None, idx, k_top, want_lse=want_lse)
+                         stats["hsum"] if first_order else None, idx, k_top, want_lse=want_lse,
+                         workspace=ws)
     return dict(out=out, lse=lse, idx=idx, kth_gap=gap, stats=stats, k_top=k_top)

@@ -23,7 +23,7 @@ def build(verbose: bool = True) -> str:
     """Always recompiles; returns the path of the shared library."""
     cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-Wno-unused-command-line-argument",
+           "-Wno-unused-command-line-argument", "-Wno-inline-asm",
            "-I", os.path.join(ROOT, "include"), "-I", CSRC,
            "-o", LIB_PATH] + [os.path.join(CSRC, s) for s in SOURCES]
     if verbose:

@@ -93,7 +93,7 @@ int32_t pisa_topk_count(int32_t num_blocks, double sparsity) {
 size_t pisa_workspace_bytes(const pisa_shape* shape) {
   Dims dm;
   if (resolve(shape, &dm) != PISA_OK) return 0;
-  return std::max(stats_workspace_bytes(dm), select_workspace_bytes(dm));
+  return std::max({stats_workspace_bytes(dm), select_workspace_bytes(dm), attention_workspace_bytes(dm)});
 }
 
 int32_t pisa_block_stats(const pisa_shape* shape, const void* q, const void* k, const void* v,
@@ -148,7 +148,8 @@ static int32_t run_attention(const Dims& dm, const AttnArgs& a, void* stream, co
 int32_t pisa_attention(const pisa_shape* shape, const void* q, const void* k, const void* v,
                        const float* kbar, const float* vsum, const float* hsum,
                        const int32_t* idx, int32_t k_top,
-                       void* out, float* lse, void* stream) {
+                       void* out, float* lse,
+                       void* workspace, size_t workspace_bytes, void* stream) {
   Dims dm;
   int32_t rc = resolve(shape, &dm);
   if (rc != PISA_OK) return rc;
@@ -160,7 +161,13 @@ int32_t pisa_attention(const pisa_shape* shape, const void* q, const void* k, co
     return fail(PISA_INVALID_ARG, "kbar and vsum must not be NULL when k_top < N");
   if (dm.N > kMaxBlocks)
     return fail(PISA_UNSUPPORTED, "at most %d blocks are supported (N = %d)", kMaxBlocks, dm.N);
-  AttnArgs a{q, k, v, kbar, vsum, hsum, idx, k_top, out, lse, false};
+  if (k_top < dm.N) {
+    size_t need = attention_workspace_bytes(dm);
+    if (need > 0 && !workspace) return fail(PISA_INVALID_ARG, "workspace is NULL (need %zu bytes)", need);
+    if (workspace_bytes < need)
+      return fail(PISA_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, need %zu", workspace_bytes, need);
+  }
+  AttnArgs a{q, k, v, kbar, vsum, hsum, idx, k_top, out, lse, false, workspace};
   return run_attention(dm, a, stream, "pisa_attention");
 }
 
@@ -170,7 +177,7 @@ int32_t dense_attention(const pisa_shape* shape, const void* q, const void* k, c
   int32_t rc = resolve(shape, &dm);
   if (rc != PISA_OK) return rc;
   if (!q || !k || !v || !out) return fail(PISA_INVALID_ARG, "q, k, v, out must not be NULL");
-  AttnArgs a{q, k, v, nullptr, nullptr, nullptr, nullptr, dm.N, out, lse, true};
+  AttnArgs a{q, k, v, nullptr, nullptr, nullptr, nullptr, dm.N, out, lse, true, nullptr};
   return run_attention(dm, a, stream, "dense_attention");
 }
 

@@ -1,64 +1,71 @@
 // bf16 attention path (dense and PISA) on the gfx950 matrix cores, head_dim 128.
 //
-// One workgroup (4 wavefronts) per 64-row query tile.  Wave w = (kh, qh): query half
-// qh (32 rows) x key half kh (32 of the 64 keys of every tile).  Each wave keeps its own
-// online-softmax state; the two key halves are merged through LDS at the end.
+// Workgroup = 4 wavefronts = 128 query rows (two adjacent 64-row query blocks, or one
+// 128-row block); wave w owns rows 32w..32w+31 and sees every key of a staged tile.
+// Two workgroups fit a CU (2 x 66 KB LDS, <= 256 VGPRs), so barrier stalls of one are
+// covered by the other.
 //
-// Everything is computed transposed, with v_mfma_f32_32x32x16_bf16:
-//     S^T (keys x queries) = K_tile (keys x d)  *  Q^T (d x queries)
-//     O^T (d    x queries) = V_tile^T (d x keys) * P^T (keys x queries)
-// so that a lane owns one query column: row max / row sum are in-lane reductions plus one
-// cross-half exchange, the rescale factor is a per-lane scalar, and the fp32 S^T
+// Everything is computed transposed with v_mfma_f32_32x32x16_bf16:
+//     S^T (keys x queries) = K_tile (keys x d)   *  Q^T (d x queries)
+//     O^T (d    x queries) = V_tile^T (d x keys) *  P^T (keys x queries)
+// A lane therefore owns one query column: row max / row sum are in-lane reductions plus
+// one exchange with lane^32, the rescale factor is a per-lane scalar, and the fp32 S^T
 // accumulator converts in place into the bf16 B operand of the second product (the key
 // order inside a contraction step is permuted identically on the V side).
-// V is staged row-major; a lane reads 8 bytes = channels 4*lane..4*lane+3 of one key and
-// byte-permutes eight such reads into the four A operands whose row `lane` stands for
-// channel 4*lane + dt (dt = 0..3), i.e. output tile dt holds channels = dt (mod 4).
 //
-// The three phases of Alg. 1 share the tile routine:
-//   Phase 1  K/V tiles of the selected blocks (all tiles for dense attention), global ->
-//            registers -> LDS, double buffered;
-//   Phase 2  tiles of 64 centroids: kbar split into bf16 hi + lo parts (two MFMA chains, so
-//            the centroid logits keep fp32-level accuracy), logit + log2 B_j, selected
-//            columns masked, values vsum_j / B_j; the mass also accumulates into l_tail;
-//   Phase 3  O += (l_tail / L) s Q hsum with hsum split hi + lo, then division by l.
+// Staging: K and V tiles (64 rows x 256 B) go global -> LDS with global_load_lds_dwordx4
+// (no registers in between), double buffered, one barrier per tile.  A wave-load writes
+// 1 KB of consecutive LDS, so bank conflicts are avoided by permuting which global chunk
+// each lane fetches: K rows XOR their 16-byte chunk index with (row & 15) (conflict-free
+// ds_read_b128 of one chunk from 16 different rows); V rows XOR their 32-byte chunk index
+// with (row & 7) (conflict-free ds_read_b64_tr_b16, which hands a 16-lane group a
+// 16-channel x 4-key transposed fragment, i.e. the V^T operand straight from row-major V).
+//
+// PISA, block 64: the two query blocks of a workgroup walk the UNION of their selected
+// key blocks in ascending order (bit scan over two LDS bitmasks); a tile selected by only
+// one block is skipped by the other block's waves.  Every shared tile halves the L2->LDS
+// traffic per flop.  Phase 2 streams bf16 centroid tiles prepared by a small pre-pass
+// (kbar split into hi + lo parts so centroid logits keep fp32-level accuracy; vsum / B_j;
+// log2 B_j), Phase 3 multiplies by the pre-packed hi/lo split of hsum.
 #include "common.h"
 
 namespace pisa {
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+#define LDS_PTR(T) __attribute__((address_space(3))) T*
+#define GLB_PTR(T) const __attribute__((address_space(1))) T*
 
 constexpr int D = 128;
-constexpr int KPITCH = 272;                 // bytes per staged key row (256 + 16 pad)
-constexpr int VPITCH = 256;                 // bytes per staged value row
-constexpr int KBYTES = kTile * KPITCH;      // 17408
-constexpr int VBYTES = kTile * VPITCH;      // 16384
-constexpr int BUFBYTES = KBYTES + VBYTES;   // one (K, V) stage
-constexpr int MASK_WORDS = 128;             // bitmask over blocks, N <= 4096
-constexpr int SMEM_BYTES = 2 * BUFBYTES + MASK_WORDS * 4;
-constexpr int MRG_STRIDE = 68;              // floats per lane in the merge buffer (64 + m, l, l_tail)
-static_assert(2 * KBYTES + VBYTES + 256 <= 2 * BUFBYTES, "phase-2 staging must fit");
-static_assert(2 * 64 * MRG_STRIDE * 4 <= 2 * BUFBYTES, "merge buffer must fit");
+constexpr int ROWB = 256;                    // bytes per staged row
+constexpr int TILEB = kTile * ROWB;          // 16 KB: one staged K or V tile
+constexpr int QROWS = 128;                   // query rows per workgroup
+constexpr int MASK_WORDS = kMaxBlocks / 32;  // 128 words per block bitmask
 
 struct PB {
   const __bf16* q;
   const __bf16* k;
   const __bf16* v;
-  const float* kbar;
-  const float* vsum;
-  const float* hsum;
+  const __bf16* khi;      // [bh][npad][128] centroid hi parts        (pre-pass)
+  const __bf16* klo;      // [bh][npad][128] centroid lo parts
+  const __bf16* vbar;     // [bh][npad][128] vsum_j / B_j
+  const float* bias;      // [npad] log2 B_j, -inf past N
+  const __bf16* hpack;    // [bh][2][8 ks][4 dt][64 lanes][8] hsum^T hi / lo in A-operand order
   const int32_t* idx;
   __bf16* out;
   float* lse;
-  int L, B, N, k_top, nqt, total;
+  int L, B, N, k_top, npad, n_super, total;
   float scale;
-  int dense;
+  int first_order;
 };
 
 __device__ inline unsigned int pack_bf16(float lo, float hi) {
@@ -67,68 +74,171 @@ __device__ inline unsigned int pack_bf16(float lo, float hi) {
   return __builtin_bit_cast(unsigned int, b);
 }
 __device__ inline float bf16_bits_to_f32(unsigned int bits16) { return __uint_as_float(bits16 << 16); }
-
-// Splits x into bf16 hi + bf16 lo (x ~ hi + lo); returns hi in the low 16 bits, lo in the high.
 __device__ inline void split_bf16(float x, unsigned int& hi, unsigned int& lo) {
-  const unsigned int p = pack_bf16(x, 0.f);
-  hi = p & 0xffffu;
-  const float r = x - bf16_bits_to_f32(hi);
-  lo = pack_bf16(r, 0.f) & 0xffffu;
+  hi = pack_bf16(x, 0.f) & 0xffffu;
+  lo = pack_bf16(x - bf16_bits_to_f32(hi), 0.f) & 0xffffu;
 }
 
+// ---------------------------------------------------------------------------------
+// Pre-pass for PISA: centroid tiles and hsum in the forms the main kernel consumes.
+// grid (npad/64 + 1, bh); the extra block of each head packs hsum.
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void attn_prep_kernel(
+    const float* __restrict__ kbar, const float* __restrict__ vsum, const float* __restrict__ hsum,
+    __bf16* __restrict__ khi, __bf16* __restrict__ klo, __bf16* __restrict__ vbar,
+    float* __restrict__ bias, __bf16* __restrict__ hpack, int L, int B, int N, int npad) {
+  const int tid = threadIdx.x;
+  const size_t bh = blockIdx.y;
+  const int g = blockIdx.x;
+  const int last_rows = L - (N - 1) * B;
+  if (g < npad / kTile) {
+    const float* kb = kbar + bh * (size_t)N * D;
+    const float* vs = vsum + bh * (size_t)N * D;
+    unsigned char* oh = reinterpret_cast<unsigned char*>(khi + bh * (size_t)npad * D);
+    unsigned char* ol = reinterpret_cast<unsigned char*>(klo + bh * (size_t)npad * D);
+    unsigned char* ov = reinterpret_cast<unsigned char*>(vbar + bh * (size_t)npad * D);
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int ch = it * 256 + tid;
+      const int n = ch >> 5, c4 = (ch & 31) * 4;
+      const int j = g * kTile + n;
+      float4 kv = make_float4(0.f, 0.f, 0.f, 0.f), vv = kv;
+      if (j < N) {
+        const float inv = 1.f / (float)(j == N - 1 ? last_rows : B);
+        kv = *reinterpret_cast<const float4*>(kb + (size_t)j * D + c4);
+        vv = *reinterpret_cast<const float4*>(vs + (size_t)j * D + c4);
+        vv.x *= inv; vv.y *= inv; vv.z *= inv; vv.w *= inv;
+      }
+      unsigned int h0, l0, h1, l1, h2, l2, h3, l3;
+      split_bf16(kv.x, h0, l0);
+      split_bf16(kv.y, h1, l1);
+      split_bf16(kv.z, h2, l2);
+      split_bf16(kv.w, h3, l3);
+      const u32x2 hi = {h0 | (h1 << 16), h2 | (h3 << 16)};
+      const u32x2 lo = {l0 | (l1 << 16), l2 | (l3 << 16)};
+      const u32x2 vb = {pack_bf16(vv.x, vv.y), pack_bf16(vv.z, vv.w)};
+      const size_t o = (size_t)j * ROWB + c4 * 2;
+      *reinterpret_cast<u32x2*>(oh + o) = hi;
+      *reinterpret_cast<u32x2*>(ol + o) = lo;
+      *reinterpret_cast<u32x2*>(ov + o) = vb;
+    }
+    if (bh == 0 && tid < kTile) {
+      const int j = g * kTile + tid;
+      bias[j] = j < N ? __builtin_amdgcn_logf((float)(j == N - 1 ? last_rows : B)) : -INFINITY;
+    }
+  } else if (hsum) {
+    // hpack[part][ks][dt][lane][e] = part(hsum[d_in = 16 ks + 8 h + e][d_out = 32 dt + lam])
+    const float* hs = hsum + bh * (size_t)D * D;
+    __bf16* hp = hpack + bh * (size_t)(2 * D * D);
+    for (int o = tid; o < D * D; o += 256) {
+      const int e = o & 7, lane = (o >> 3) & 63, dt = (o >> 9) & 3, ks = o >> 11;
+      const int lam = lane & 31, h = lane >> 5;
+      const float x = hs[(size_t)(16 * ks + 8 * h + e) * D + 32 * dt + lam];
+      unsigned int hi, lo;
+      split_bf16(x, hi, lo);
+      reinterpret_cast<unsigned short*>(hp)[o] = (unsigned short)hi;
+      reinterpret_cast<unsigned short*>(hp)[D * D + o] = (unsigned short)lo;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// Main kernel
+// ---------------------------------------------------------------------------------
 struct State {
-  f32x16 ot[4];      // O^T tiles: ot[dt][r] <-> channel 4*rho + dt, rho = (r/4)*8 + 4h + r%4
-  float m;           // running max (log2 domain, includes the scale)
-  float l;           // this lane's share of the row sum
+  f32x16 ot[4];      // O^T tiles: ot[dt][r] <-> channel 32 dt + (r/4)*8 + 4h + r%4
+  float m;           // running max (log2 domain, scale included)
+  float l;           // this lane's share of the row sum (keys with its h)
   float l_tail;      // this lane's share of the tail mass
 };
 
-// One 64-key tile.  kA/kB: staged key rows (TAIL: hi and lo parts), vS: staged value rows.
-// bias (TAIL only): 64 floats, log2 B_j or -inf.  nvalid: valid keys in the tile (Phase 1).
+// Asynchronous load of a 64-row tile of a row-major matrix with 256-byte rows into LDS.
+// KFMT: 16-byte chunks XOR (row & 15); else 32-byte chunks XOR (row & 7).
+// Rows past `max_row` are replaced by row `max_row` (finite data; such keys are masked).
+// The LDS-DMA instruction is issued through inline asm on purpose: the compiler then does
+// not track it, so it places no vmcnt wait in front of later LDS reads of the *other*
+// stage; completion is enforced by wait_async_loads() + barrier before a stage is read.
+template <bool KFMT>
+__device__ inline void load_tile_async(const unsigned char* gbase, int row0, int max_row,
+                                       LDS_PTR(unsigned char) dst, int wave, int lane) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int wl = wave * 4 + i;                 // which KB of the tile this wave fills
+    const int r = wl * 4 + (lane >> 4);          // tile row
+    const int pos = lane & 15;                   // 16-byte slot inside the LDS row
+    const int chunk = KFMT ? (pos ^ (r & 15)) : ((((pos >> 1) ^ (r & 7)) << 1) | (pos & 1));
+    const int grow = min(row0 + r, max_row);
+    const unsigned char* src = gbase + (size_t)grow * ROWB + chunk * 16;
+    const unsigned int lds_addr =
+        __builtin_amdgcn_readfirstlane((unsigned int)(unsigned long long)(dst + wl * 1024));
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(lds_addr), "v"(src)
+                 : "memory", "m0");
+  }
+}
+
+// One staged 64-key tile folded into the wave's state.
+//   kA (and kB when TAIL: hi, lo parts): K-format tiles; vS: V-format tile.
+//   bias (TAIL only): 64 floats in LDS: log2 B_j, or -inf for masked / absent columns.
+//   nvalid: valid keys of the tile (Phase 1; keys >= nvalid are masked).
 template <bool TAIL>
-__device__ inline void absorb_tile(State& st, const bf16x8 (&qreg)[8], const unsigned char* kA,
-                                   const unsigned char* kB, const unsigned char* vS,
-                                   const float* bias, int nvalid, float c, int lam, int h, int kh) {
-  f32x16 s = {0};
-  const unsigned char* krow = kA + (32 * kh + lam) * KPITCH + 16 * h;
+__device__ inline void absorb_tile(State& st, const bf16x8 (&qreg)[8], LDS_PTR(const unsigned char) kA,
+                                   LDS_PTR(const unsigned char) kB, LDS_PTR(const unsigned char) vS,
+                                   LDS_PTR(const float) bias, int nvalid, float c, int lane) {
+  const int lam = lane & 31, h = lane >> 5;
+  f32x16 s0 = {0}, s1 = {0};
+  {
+    const int rowoff = lam * ROWB;
+    const int sw = lam & 15;
+    constexpr int NK = TAIL ? 16 : 8;              // TAIL: hi chain then lo chain
+    auto kread = [&](int i, bf16x8& a0, bf16x8& a1) {
+      LDS_PTR(const unsigned char) base = (TAIL && i >= 8) ? kB : kA;
+      const int off = rowoff + (((2 * (i & 7) + h) ^ sw) << 4);
+      a0 = *reinterpret_cast<LDS_PTR(const bf16x8)>(base + off);
+      a1 = *reinterpret_cast<LDS_PTR(const bf16x8)>(base + off + 32 * ROWB);
+    };
+    bf16x8 ka[3][2];
+    kread(0, ka[0][0], ka[0][1]);
+    kread(1, ka[1][0], ka[1][1]);
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) {
-    const bf16x8 a = *reinterpret_cast<const bf16x8*>(krow + 32 * ks);
-    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], s, 0, 0, 0);
-  }
-  if (TAIL) {
-    const unsigned char* krow2 = kB + (32 * kh + lam) * KPITCH + 16 * h;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>(krow2 + 32 * ks);
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], s, 0, 0, 0);
+    for (int i = 0; i < NK; ++i) {
+      if (i + 2 < NK) kread(i + 2, ka[(i + 2) % 3][0], ka[(i + 2) % 3][1]);
+      s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[i % 3][0], qreg[i & 7], s0, 0, 0, 0);
+      s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[i % 3][1], qreg[i & 7], s1, 0, 0, 0);
     }
   }
-  // ---- logits in the log2 domain, masks ----
-  float x[16];
+  // ---- logits in the log2 domain; register r of half kk <-> key 32 kk + (r/4)*8 + 4h + r%4 ----
+  float x[32];
   if (TAIL) {
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      const float4 b = *reinterpret_cast<const float4*>(bias + 32 * kh + 8 * g + 4 * h);
-      x[4 * g + 0] = fmaf(s[4 * g + 0], c, b.x);
-      x[4 * g + 1] = fmaf(s[4 * g + 1], c, b.y);
-      x[4 * g + 2] = fmaf(s[4 * g + 2], c, b.z);
-      x[4 * g + 3] = fmaf(s[4 * g + 3], c, b.w);
-    }
+    for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const f32x4 b = *reinterpret_cast<LDS_PTR(const f32x4)>(bias + 32 * kk + 8 * g + 4 * h);
+        const f32x16& s = kk ? s1 : s0;
+        x[16 * kk + 4 * g + 0] = fmaf(s[4 * g + 0], c, b.x);
+        x[16 * kk + 4 * g + 1] = fmaf(s[4 * g + 1], c, b.y);
+        x[16 * kk + 4 * g + 2] = fmaf(s[4 * g + 2], c, b.z);
+        x[16 * kk + 4 * g + 3] = fmaf(s[4 * g + 3], c, b.w);
+      }
   } else {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) x[r] = s[r] * c;
+    for (int r = 0; r < 16; ++r) {
+      x[r] = s0[r] * c;
+      x[16 + r] = s1[r] * c;
+    }
     if (nvalid < kTile) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int key = 32 * kh + (r / 4) * 8 + 4 * h + (r % 4);
+      for (int r = 0; r < 32; ++r) {
+        const int key = 32 * (r >> 4) + ((r & 15) / 4) * 8 + 4 * h + (r % 4);
         if (key >= nvalid) x[r] = -INFINITY;
       }
     }
   }
   float tmax = x[0];
 #pragma unroll
-  for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, x[r]);
+  for (int r = 1; r < 32; ++r) tmax = fmaxf(tmax, x[r]);
   tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
   const float m_new = fmaxf(st.m, tmax);
   const float m_safe = m_new == -INFINITY ? 0.f : m_new;
@@ -140,81 +250,83 @@ __device__ inline void absorb_tile(State& st, const bf16x8 (&qreg)[8], const uns
     for (int dt = 0; dt < 4; ++dt) st.ot[dt] *= corr;
     st.m = m_new;
   }
-  float pe[16];
   float psum = 0.f;
 #pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    pe[r] = __builtin_amdgcn_exp2f(x[r] - m_safe);
-    psum += pe[r];
+  for (int r = 0; r < 32; ++r) {
+    x[r] = __builtin_amdgcn_exp2f(x[r] - m_safe);
+    psum += x[r];
   }
   st.l += psum;
   if (TAIL) st.l_tail += psum;
-  // ---- O^T += V^T P^T ----
+  // ---- O^T += V^T P^T: four contraction steps of 16 keys ----
+  // Transposed LDS read: lane j of a 16-lane group points at 4 channels of key (j >> 2);
+  // it receives channel (group base + j) of the group's four keys.
+  const int j16 = lane & 15;
+  const int kq = 4 * h + (j16 >> 2);                 // key offset of this lane's pointer, = key & 7
+  const int vlane = kq * ROWB + 8 * (j16 & 3);
+  const int lhalf = (lane >> 4) & 1;
 #pragma unroll
-  for (int s2 = 0; s2 < 2; ++s2) {
+  for (int step = 0; step < 4; ++step) {            // keys 16 step .. 16 step + 15
     u32x4 pw;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) pw[i] = pack_bf16(pe[8 * s2 + 2 * i], pe[8 * s2 + 2 * i + 1]);
+    for (int i = 0; i < 4; ++i) pw[i] = pack_bf16(x[8 * step + 2 * i], x[8 * step + 2 * i + 1]);
     const bf16x8 pb = __builtin_bit_cast(bf16x8, pw);
-    u32x2 vr[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int key = 32 * kh + (2 * s2 + e / 4) * 8 + 4 * h + (e % 4);
-      vr[e] = *reinterpret_cast<const u32x2*>(vS + key * VPITCH + lam * 8);
-    }
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt) {
-      u32x4 aw;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const unsigned int w0 = (dt >> 1) ? vr[2 * i].y : vr[2 * i].x;
-        const unsigned int w1 = (dt >> 1) ? vr[2 * i + 1].y : vr[2 * i + 1].x;
-        aw[i] = __builtin_amdgcn_perm(w1, w0, (dt & 1) ? 0x07060302u : 0x05040100u);
-      }
+      const int off = 16 * step * ROWB + vlane + (((2 * dt + lhalf) ^ kq) << 5);
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          reinterpret_cast<LDS_PTR(s16x4)>(const_cast<LDS_PTR(unsigned char)>(vS + off)));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          reinterpret_cast<LDS_PTR(s16x4)>(const_cast<LDS_PTR(unsigned char)>(vS + off + 8 * ROWB)));
+      const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
+      const u32x4 aw = {l2.x, l2.y, h2.x, h2.y};
       st.ot[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, aw), pb,
                                                           st.ot[dt], 0, 0, 0);
     }
   }
 }
 
-__global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  unsigned int* chosen = reinterpret_cast<unsigned int*>(smem + 2 * BUFBYTES);
+// s_waitcnt vmcnt(0) with the other counters left alone (gfx9 encoding).
+__device__ inline void wait_async_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
-  // XCD-aware order: consecutive workgroup ids land on different XCDs, so give each of
-  // the 8 XCDs a contiguous range of (head, query tile) items; its L2 then sees one head.
+template <bool DENSE>
+__global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
+  __shared__ __attribute__((aligned(1024))) unsigned char stage[2][2 * TILEB];   // [buf][K | V]
+  __shared__ unsigned int chosen[2][MASK_WORDS];
+  __shared__ __attribute__((aligned(16))) float bias_s[2][kTile];
+
+  // XCD-aware order: consecutive workgroup ids land on different XCDs, so each of the 8
+  // XCDs gets a contiguous range of (head, query super-tile) items and its L2 sees one head.
   const int wg = blockIdx.x;
   const int per_xcd = (p.total + 7) / 8;
   const int item = (wg % 8) * per_xcd + wg / 8;
   if (item >= p.total) return;
-  const size_t bh = item / p.nqt;
-  const int qt = item % p.nqt;
+  const size_t bh = item / p.n_super;
+  const int sg = item % p.n_super;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int lam = lane & 31, h = lane >> 5;
-  const int qh = wave & 1, kh = wave >> 1;
   const int L = p.L, N = p.N;
-  const __bf16* qg = p.q + bh * (size_t)L * D;
-  const __bf16* kg = p.k + bh * (size_t)L * D;
-  const __bf16* vg = p.v + bh * (size_t)L * D;
-  const int tpb = p.B / kTile;
-  const int32_t* my_idx = p.dense ? nullptr : p.idx + (bh * N + qt / tpb) * (size_t)p.k_top;
+  const unsigned char* kg = reinterpret_cast<const unsigned char*>(p.k + bh * (size_t)L * D);
+  const unsigned char* vg = reinterpret_cast<const unsigned char*>(p.v + bh * (size_t)L * D);
+  const int tpb = p.B / kTile;                       // tiles per block: 1 or 2
+  const int qb = tpb == 1 ? (wave >> 1) : 0;         // which of the workgroup's query blocks
   const float c = p.scale * 1.44269504088896340736f;
+  LDS_PTR(unsigned char) lds = (LDS_PTR(unsigned char)) & stage[0][0];
 
-  // ---- Q^T operand: this lane's query row, 8 channel slices ----
-  const int q_row = qt * kTile + 32 * qh + lam;
+  // ---- Q^T operand: this lane's query row, 8 channel slices of 16 ----
+  const int q_row = sg * QROWS + 32 * wave + lam;
   bf16x8 qreg[8];
   {
-    const u32x4 zero = {0, 0, 0, 0};
+    const __bf16* qg = p.q + bh * (size_t)L * D;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
-      u32x4 w = zero;
+      u32x4 w = {0, 0, 0, 0};
       if (q_row < L) w = *reinterpret_cast<const u32x4*>(qg + (size_t)q_row * D + 16 * ks + 8 * h);
       qreg[ks] = __builtin_bit_cast(bf16x8, w);
     }
   }
-  if (tid < MASK_WORDS) chosen[tid] = 0u;
 
   State st;
 #pragma unroll
@@ -223,220 +335,169 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
   st.l = 0.f;
   st.l_tail = 0.f;
 
-  // ---- Phase 1 ----
-  const int n1 = p.dense ? (L + kTile - 1) / kTile : p.k_top * tpb;
-  auto tile_of = [&](int t) -> int { return p.dense ? t : my_idx[t / tpb] * tpb + (t % tpb); };
-  u32x4 kr[4], vr[4];
-  auto fetch = [&](int tile) {
-    const int row0 = tile * kTile;
-#pragma unroll
-    for (int it = 0; it < 4; ++it) {
-      const int ch = it * 256 + tid;
-      const int row = row0 + (ch >> 4), col = ch & 15;
-      const u32x4 zero = {0, 0, 0, 0};
-      kr[it] = zero;
-      vr[it] = zero;
-      if (row < L) {
-        kr[it] = *reinterpret_cast<const u32x4*>(kg + (size_t)row * D + col * 8);
-        vr[it] = *reinterpret_cast<const u32x4*>(vg + (size_t)row * D + col * 8);
+  // ---- block bitmasks of the workgroup's query block(s) ----
+  const int nwords = (N + 31) / 32;
+  if (!DENSE) {
+    for (int w = tid; w < 2 * MASK_WORDS; w += 256) (&chosen[0][0])[w] = 0u;
+    __syncthreads();
+    const int nqb = tpb == 1 ? 2 : 1;
+    for (int b = 0; b < nqb; ++b) {
+      const int i = tpb == 1 ? 2 * sg + b : sg;
+      if (i < N) {
+        const int32_t* row = p.idx + (bh * N + i) * (size_t)p.k_top;
+        for (int t = tid; t < p.k_top; t += 256) {
+          const int j = row[t];
+          atomicOr(&chosen[b][j >> 5], 1u << (j & 31));
+        }
       }
     }
-  };
-  auto stage = [&](int buf) {
-    unsigned char* kS = smem + buf * BUFBYTES;
-    unsigned char* vS = kS + KBYTES;
-#pragma unroll
-    for (int it = 0; it < 4; ++it) {
-      const int ch = it * 256 + tid;
-      const int row = ch >> 4, col = ch & 15;
-      *reinterpret_cast<u32x4*>(kS + row * KPITCH + col * 16) = kr[it];
-      *reinterpret_cast<u32x4*>(vS + row * VPITCH + col * 16) = vr[it];
-    }
-  };
-  int tile_cur = 0;
-  if (n1 > 0) {
-    tile_cur = tile_of(0);
-    fetch(tile_cur);
-    stage(0);
-  }
-  __syncthreads();
-  if (!p.dense) {
-    for (int t = tid; t < p.k_top; t += 256) {
-      const int j = my_idx[t];
-      atomicOr(&chosen[j >> 5], 1u << (j & 31));
-    }
-  }
-  for (int t = 0; t < n1; ++t) {
-    const int buf = t & 1;
-    int tile_next = 0;
-    if (t + 1 < n1) {
-      tile_next = tile_of(t + 1);
-      fetch(tile_next);
-    }
-    const unsigned char* kS = smem + buf * BUFBYTES;
-    const int nvalid = min(kTile, L - tile_cur * kTile);
-    absorb_tile<false>(st, qreg, kS, nullptr, kS + KBYTES, nullptr, nvalid, c, lam, h, kh);
-    if (t + 1 < n1) stage(buf ^ 1);
-    tile_cur = tile_next;
     __syncthreads();
   }
 
-  // ---- Phase 2 ----
-  const bool approx = !p.dense && p.k_top < N;
+  // ---- Phase 1: walk the exact tiles (all tiles; or the union of the selected blocks) ----
+  const int n_tiles = (L + kTile - 1) / kTile;
+  int w_word = -1, pend = -1, pend_in = 0, dense_t = 0;
+  unsigned int w_union = 0u, w_m0 = 0u, w_m1 = 0u;
+  auto next_tile = [&](int& tile, int& inmask) -> bool {
+    if (DENSE) {
+      if (dense_t >= n_tiles) return false;
+      tile = dense_t++;
+      inmask = 3;
+      return true;
+    }
+    if (pend >= 0) {
+      tile = pend;
+      inmask = pend_in;
+      pend = -1;
+      return true;
+    }
+    while (w_union == 0u) {
+      if (++w_word >= nwords) return false;
+      w_m0 = chosen[0][w_word];
+      w_m1 = chosen[1][w_word];
+      w_union = __builtin_amdgcn_readfirstlane(w_m0 | w_m1);
+    }
+    const int b = __builtin_ctz(w_union);
+    w_union &= w_union - 1u;
+    const int j = w_word * 32 + b;
+    inmask = __builtin_amdgcn_readfirstlane(((w_m0 >> b) & 1u) | (((w_m1 >> b) & 1u) << 1));
+    if (tpb == 1) {
+      tile = j;
+    } else {
+      tile = 2 * j;
+      inmask = inmask ? 3 : 0;
+      if ((2 * j + 1) * kTile < L) {
+        pend = 2 * j + 1;
+        pend_in = inmask;
+      }
+    }
+    return true;
+  };
+
+  int tile_cur = 0, in_cur = 0, tile_nxt = 0, in_nxt = 0;
+  bool have = next_tile(tile_cur, in_cur);
+  if (have) {
+    load_tile_async<true>(kg, tile_cur * kTile, L - 1, lds, wave, lane);
+    load_tile_async<false>(vg, tile_cur * kTile, L - 1, lds + TILEB, wave, lane);
+  }
+  int buf = 0;
+  while (have) {
+    const bool have_nxt = next_tile(tile_nxt, in_nxt);
+    wait_async_loads();
+    __syncthreads();   // tile `cur` is complete in stage[buf]; stage[buf^1] is no longer read
+    if (have_nxt) {
+      LDS_PTR(unsigned char) dst = lds + (buf ^ 1) * 2 * TILEB;
+      load_tile_async<true>(kg, tile_nxt * kTile, L - 1, dst, wave, lane);
+      load_tile_async<false>(vg, tile_nxt * kTile, L - 1, dst + TILEB, wave, lane);
+    }
+    if ((in_cur >> qb) & 1) {
+      LDS_PTR(const unsigned char) kS = lds + buf * 2 * TILEB;
+      const int nvalid = min(kTile, L - tile_cur * kTile);
+      absorb_tile<false>(st, qreg, kS, kS, kS + TILEB, nullptr, nvalid, c, lane);
+    }
+    tile_cur = tile_nxt;
+    in_cur = in_nxt;
+    have = have_nxt;
+    buf ^= 1;
+  }
+
+  // ---- Phase 2: centroid tiles (hi, lo, values) ----
+  const bool approx = !DENSE && p.k_top < N;
   if (approx) {
-    unsigned char* kHi = smem;
-    unsigned char* kLo = smem + KBYTES;
-    unsigned char* vS = smem + 2 * KBYTES;
-    float* bias = reinterpret_cast<float*>(smem + 2 * KBYTES + VBYTES);
-    const float* kb = p.kbar + bh * (size_t)N * D;
-    const float* vs = p.vsum + bh * (size_t)N * D;
-    const int last_rows = L - (N - 1) * p.B;
+    const unsigned char* khg = reinterpret_cast<const unsigned char*>(p.khi + bh * (size_t)p.npad * D);
+    const unsigned char* klg = reinterpret_cast<const unsigned char*>(p.klo + bh * (size_t)p.npad * D);
+    const unsigned char* vbg = reinterpret_cast<const unsigned char*>(p.vbar + bh * (size_t)p.npad * D);
+    LDS_PTR(const float) my_bias = (LDS_PTR(const float)) & bias_s[qb][0];
     for (int g0 = 0; g0 < N; g0 += kTile) {
-#pragma unroll
-      for (int it = 0; it < 8; ++it) {
-        const int ch = it * 256 + tid;            // float4 chunk: row = ch / 32, col4 = ch % 32
-        const int n = ch >> 5, c4 = (ch & 31) * 4;
-        const int j = g0 + n;
-        float4 kv = make_float4(0.f, 0.f, 0.f, 0.f), vv = kv;
-        if (j < N) {
-          const float inv = 1.f / (float)(j == N - 1 ? last_rows : p.B);
-          kv = *reinterpret_cast<const float4*>(kb + (size_t)j * D + c4);
-          vv = *reinterpret_cast<const float4*>(vs + (size_t)j * D + c4);
-          vv.x *= inv; vv.y *= inv; vv.z *= inv; vv.w *= inv;
-        }
-        unsigned int h0, l0, h1, l1, h2, l2, h3, l3;
-        split_bf16(kv.x, h0, l0);
-        split_bf16(kv.y, h1, l1);
-        split_bf16(kv.z, h2, l2);
-        split_bf16(kv.w, h3, l3);
-        u32x2 hi = {h0 | (h1 << 16), h2 | (h3 << 16)};
-        u32x2 lo = {l0 | (l1 << 16), l2 | (l3 << 16)};
-        u32x2 vb = {pack_bf16(vv.x, vv.y), pack_bf16(vv.z, vv.w)};
-        *reinterpret_cast<u32x2*>(kHi + n * KPITCH + c4 * 2) = hi;
-        *reinterpret_cast<u32x2*>(kLo + n * KPITCH + c4 * 2) = lo;
-        *reinterpret_cast<u32x2*>(vS + n * VPITCH + c4 * 2) = vb;
+      __syncthreads();                         // previous tile fully consumed
+      load_tile_async<true>(khg, g0, p.npad - 1, lds, wave, lane);
+      load_tile_async<true>(klg, g0, p.npad - 1, lds + TILEB, wave, lane);
+      load_tile_async<false>(vbg, g0, p.npad - 1, lds + 2 * TILEB, wave, lane);
+      if (tid < 2 * kTile) {
+        const int b = tid >> 6, j = g0 + (tid & 63);
+        const bool masked = tpb == 2 && b == 1 ? true : ((chosen[b][(j >> 5) & (MASK_WORDS - 1)] >> (j & 31)) & 1u);
+        bias_s[b][tid & 63] = masked ? -INFINITY : p.bias[j];
       }
-      if (tid < kTile) {
-        const int j = g0 + tid;
-        float b = -INFINITY;
-        if (j < N && !((chosen[j >> 5] >> (j & 31)) & 1u))
-          b = __builtin_amdgcn_logf((float)(j == N - 1 ? last_rows : p.B));   // log2
-        bias[tid] = b;
-      }
+      wait_async_loads();
       __syncthreads();
-      absorb_tile<true>(st, qreg, kHi, kLo, vS, bias, kTile, c, lam, h, kh);
-      __syncthreads();
+      absorb_tile<true>(st, qreg, lds, lds + TILEB, lds + 2 * TILEB, my_bias, kTile, c, lane);
     }
   }
 
-  // ---- merge the two key halves ----
+  // ---- combine the two lane halves (keys with h = 0 / h = 1) ----
   st.l += __shfl_xor(st.l, 32);
   st.l_tail += __shfl_xor(st.l_tail, 32);
-  float* mrg = reinterpret_cast<float*>(smem) + qh * 64 * MRG_STRIDE;
-  if (kh == 1) {
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mrg[(dt * 16 + r) * 64 + lane] = st.ot[dt][r];
-    mrg[64 * 64 + lane] = st.m;
-    mrg[65 * 64 + lane] = st.l;
-    mrg[66 * 64 + lane] = st.l_tail;
-  }
-  __syncthreads();
-  if (kh == 1) return;
-  {
-    const float m1 = mrg[64 * 64 + lane], l1 = mrg[65 * 64 + lane], t1 = mrg[66 * 64 + lane];
-    const float ms = fmaxf(st.m, m1);
-    const float a0 = __builtin_amdgcn_exp2f(st.m - ms), a1 = __builtin_amdgcn_exp2f(m1 - ms);
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r)
-        st.ot[dt][r] = st.ot[dt][r] * a0 + mrg[(dt * 16 + r) * 64 + lane] * a1;
-    st.l = st.l * a0 + l1 * a1;
-    st.l_tail = st.l_tail * a0 + t1 * a1;
-    st.m = ms;
-  }
 
-  // ---- Phase 3: R^T = hsum^T (d_out x d_in) * Q^T (d_in x queries), weight l_tail/L * s ----
-  if (approx && p.hsum) {
-    const float* hs = p.hsum + bh * (size_t)D * D;
+  // ---- Phase 3: R^T = hsum^T (d_out x d_in) * Q^T (d_in x queries), weight l_tail / L * s ----
+  if (approx && p.first_order) {
+    const bf16x8* hp = reinterpret_cast<const bf16x8*>(p.hpack + bh * (size_t)(2 * D * D));
     f32x16 rt[4];
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt) rt[dt] = (f32x16){0};
-    for (int ks = 0; ks < 8; ++ks) {
-      float4 hv[8];
 #pragma unroll
-      for (int e = 0; e < 8; ++e)
-        hv[e] = *reinterpret_cast<const float4*>(hs + (size_t)(16 * ks + 8 * h + e) * D + 4 * lam);
+    for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
       for (int dt = 0; dt < 4; ++dt) {
-        u32x4 ahi, alo;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const float x0 = dt == 0 ? hv[2 * i].x : dt == 1 ? hv[2 * i].y : dt == 2 ? hv[2 * i].z : hv[2 * i].w;
-          const float x1 = dt == 0 ? hv[2 * i + 1].x : dt == 1 ? hv[2 * i + 1].y
-                         : dt == 2 ? hv[2 * i + 1].z : hv[2 * i + 1].w;
-          unsigned int h0, l0, h1, l1;
-          split_bf16(x0, h0, l0);
-          split_bf16(x1, h1, l1);
-          ahi[i] = h0 | (h1 << 16);
-          alo[i] = l0 | (l1 << 16);
-        }
-        rt[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ahi), qreg[ks],
-                                                         rt[dt], 0, 0, 0);
-        rt[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, alo), qreg[ks],
-                                                         rt[dt], 0, 0, 0);
+        const bf16x8 ahi = hp[(ks * 4 + dt) * 64 + lane];
+        const bf16x8 alo = hp[D * D / 8 + (ks * 4 + dt) * 64 + lane];
+        rt[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ahi, qreg[ks], rt[dt], 0, 0, 0);
+        rt[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(alo, qreg[ks], rt[dt], 0, 0, 0);
       }
-    }
     const float w = st.l_tail / (float)L * p.scale;
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt) st.ot[dt] += rt[dt] * w;
   }
 
-  // ---- normalise and store ----
+  // ---- normalise and store: register group g of tile dt = channels 32 dt + 8 g + 4 h + 0..3 ----
   if (q_row < L) {
     const float inv_l = 1.f / st.l;
     __bf16* orow = p.out + (bh * (size_t)L + q_row) * D;
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      // registers 4g..4g+3 of the four tiles: channels 32g + 16h + 0..15
-      u32x4 w0, w1;
+    for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-      for (int rr = 0; rr < 2; ++rr) {
-        const int r = 4 * g + rr;
-        w0[2 * rr] = pack_bf16(st.ot[0][r] * inv_l, st.ot[1][r] * inv_l);
-        w0[2 * rr + 1] = pack_bf16(st.ot[2][r] * inv_l, st.ot[3][r] * inv_l);
-        const int r2 = 4 * g + 2 + rr;
-        w1[2 * rr] = pack_bf16(st.ot[0][r2] * inv_l, st.ot[1][r2] * inv_l);
-        w1[2 * rr + 1] = pack_bf16(st.ot[2][r2] * inv_l, st.ot[3][r2] * inv_l);
+      for (int g = 0; g < 4; ++g) {
+        const u32x2 w = {pack_bf16(st.ot[dt][4 * g] * inv_l, st.ot[dt][4 * g + 1] * inv_l),
+                         pack_bf16(st.ot[dt][4 * g + 2] * inv_l, st.ot[dt][4 * g + 3] * inv_l)};
+        *reinterpret_cast<u32x2*>(orow + 32 * dt + 8 * g + 4 * h) = w;
       }
-      *reinterpret_cast<u32x4*>(orow + 32 * g + 16 * h) = w0;
-      *reinterpret_cast<u32x4*>(orow + 32 * g + 16 * h + 8) = w1;
-    }
     if (p.lse && h == 0)
-      p.lse[bh * (size_t)L + q_row] =
-          (st.m + __builtin_amdgcn_logf(st.l)) * 0.69314718055994530942f;
+      p.lse[bh * (size_t)L + q_row] = (st.m + __builtin_amdgcn_logf(st.l)) * 0.69314718055994530942f;
   }
 }
 
 }  // namespace
 
+size_t attention_workspace_bytes(const Dims& dm) {
+  if (dm.dtype != PISA_BF16) return 0;
+  const size_t npad = (size_t)((dm.N + kTile - 1) / kTile) * kTile;
+  return (size_t)dm.bh() * (3 * npad * D * 2 + 2 * D * D * 2) + npad * sizeof(float);
+}
+
 hipError_t launch_attention_bf16(const Dims& dm, const AttnArgs& a, hipStream_t stream) {
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bf16_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
-  PB p;
+  PB p{};
   p.q = (const __bf16*)a.q;
   p.k = (const __bf16*)a.k;
   p.v = (const __bf16*)a.v;
-  p.kbar = a.kbar;
-  p.vsum = a.vsum;
-  p.hsum = a.hsum;
   p.idx = a.idx;
   p.out = (__bf16*)a.out;
   p.lse = a.lse;
@@ -444,12 +505,36 @@ hipError_t launch_attention_bf16(const Dims& dm, const AttnArgs& a, hipStream_t 
   p.B = dm.B;
   p.N = dm.N;
   p.k_top = a.k_top;
-  p.nqt = (dm.L + kTile - 1) / kTile;
-  p.total = p.nqt * dm.bh();
+  p.npad = ((dm.N + kTile - 1) / kTile) * kTile;
+  p.n_super = (dm.L + QROWS - 1) / QROWS;
+  p.total = p.n_super * dm.bh();
   p.scale = dm.scale;
-  p.dense = a.dense ? 1 : 0;
+  p.first_order = a.hsum != nullptr;
   const int grid = ((p.total + 7) / 8) * 8;
-  hipLaunchKernelGGL(attn_bf16_kernel, dim3(grid), dim3(256), SMEM_BYTES, stream, p);
+  if (a.dense) {
+    hipLaunchKernelGGL(attn_bf16_kernel<true>, dim3(grid), dim3(256), 0, stream, p);
+    return hipGetLastError();
+  }
+  if (a.k_top < dm.N) {
+    // carve the workspace: khi | klo | vbar | hpack | bias
+    unsigned char* ws = static_cast<unsigned char*>(a.workspace);
+    const size_t tile_elems = (size_t)dm.bh() * p.npad * D;
+    __bf16* khi = reinterpret_cast<__bf16*>(ws);
+    __bf16* klo = khi + tile_elems;
+    __bf16* vbar = klo + tile_elems;
+    __bf16* hpack = vbar + tile_elems;
+    float* bias = reinterpret_cast<float*>(hpack + (size_t)dm.bh() * 2 * D * D);
+    hipLaunchKernelGGL(attn_prep_kernel, dim3(p.npad / kTile + 1, dm.bh()), dim3(256), 0, stream,
+                       a.kbar, a.vsum, a.hsum, khi, klo, vbar, bias, hpack, dm.L, dm.B, dm.N, p.npad);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    p.khi = khi;
+    p.klo = klo;
+    p.vbar = vbar;
+    p.hpack = hpack;
+    p.bias = bias;
+  }
+  hipLaunchKernelGGL(attn_bf16_kernel<false>, dim3(grid), dim3(256), 0, stream, p);
   return hipGetLastError();
 }
 

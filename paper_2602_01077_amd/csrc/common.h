@@ -57,7 +57,9 @@ struct AttnArgs {
   void* out;
   float* lse;            // may be null
   bool dense;
+  void* workspace;       // scratch for the bf16 PISA pre-pass (null for dense / fp32)
 };
+size_t attention_workspace_bytes(const Dims& dm);
 hipError_t launch_attention_fp32(const Dims& dm, const AttnArgs& a, hipStream_t stream);
 hipError_t launch_attention_bf16(const Dims& dm, const AttnArgs& a, hipStream_t stream);
 

@@ -72,7 +72,7 @@ def test_bad_shapes_are_rejected(kw, code):
     s = shape(**kw)
     assert lib.dense_attention(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, None, None) == code
     assert pisa.last_error() != ""
-    assert lib.pisa_attention(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 1, FAKE, None, None) == code
+    assert lib.pisa_attention(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 1, FAKE, None, FAKE, 1 << 40, None) == code
     assert lib.pisa_select(ctypes.byref(s), FAKE, FAKE, 1, FAKE, None, FAKE, 1 << 40, None) == code
     assert lib.pisa_block_stats(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE,
                                 FAKE, 1 << 40, None) == code
@@ -83,12 +83,12 @@ def test_null_and_range_arguments():
     s = shape()
     assert lib.dense_attention(None, FAKE, FAKE, FAKE, FAKE, None, None) == pisa.PISA_INVALID_ARG
     assert lib.dense_attention(ctypes.byref(s), None, FAKE, FAKE, FAKE, None, None) == pisa.PISA_INVALID_ARG
-    assert lib.pisa_attention(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 17, FAKE, None, None) \
+    assert lib.pisa_attention(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 17, FAKE, None, FAKE, 1 << 40, None) \
         == pisa.PISA_INVALID_ARG
     assert "k_top" in pisa.last_error()
-    assert lib.pisa_attention(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, 4, FAKE, None, None) \
+    assert lib.pisa_attention(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, 4, FAKE, None, FAKE, 1 << 40, None) \
         == pisa.PISA_INVALID_ARG
-    assert lib.pisa_attention(ctypes.byref(s), FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, 4, FAKE, None, None) \
+    assert lib.pisa_attention(ctypes.byref(s), FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, 4, FAKE, None, FAKE, 1 << 40, None) \
         == pisa.PISA_INVALID_ARG
     assert lib.pisa_select(ctypes.byref(s), FAKE, FAKE, -1, FAKE, None, FAKE, 1 << 40, None) == pisa.PISA_INVALID_ARG
     assert lib.pisa_select(ctypes.byref(s), FAKE, FAKE, 4, FAKE, None, FAKE, 8, None) == pisa.PISA_WORKSPACE_TOO_SMALL
