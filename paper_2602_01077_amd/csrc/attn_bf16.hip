@@ -27,6 +27,8 @@
 // traffic per flop.  Phase 2 streams bf16 centroid tiles prepared by a small pre-pass
 // (kbar split into hi + lo parts so centroid logits keep fp32-level accuracy; vsum / B_j;
 // log2 B_j), Phase 3 multiplies by the pre-packed hi/lo split of hsum.
+#include <type_traits>
+
 #include "common.h"
 
 namespace pisa {
@@ -152,64 +154,91 @@ struct State {
   float l_tail;      // this lane's share of the tail mass
 };
 
-// Asynchronous load of a 64-row tile of a row-major matrix with 256-byte rows into LDS.
-// KFMT: 16-byte chunks XOR (row & 15); else 32-byte chunks XOR (row & 7).
-// Rows past `max_row` are replaced by row `max_row` (finite data; such keys are masked).
-// The LDS-DMA instruction is issued through inline asm on purpose: the compiler then does
-// not track it, so it places no vmcnt wait in front of later LDS reads of the *other*
-// stage; completion is enforced by wait_async_loads() + barrier before a stage is read.
+// Per-lane constants of the staging layout, computed once per kernel.
+// LDS-DMA: wave w fills KB numbers w, w+4, w+8, w+12 of a staged 16 KB tile, i.e. tile rows
+// r0 + 16 i with r0 = 4 w + lane/16; rows 16 apart share their swizzle, so one per-lane
+// byte offset per format serves all four loads (the +4096 i goes into the scalar base).
+struct LaneCtx {
+  unsigned dma_k, dma_v;   // byte offset inside a global tile: K format / V format
+  int dma_r0;              // tile row of the first load
+  unsigned wave;           // wave index (uniform)
+  LDS_PTR(const unsigned char) kbase;   // K operand address of contraction step 0
+  LDS_PTR(const unsigned char) vbase;   // V^T operand address of channel tile 0
+  int h;
+};
+
+// Asynchronous global -> LDS load of one 64-row tile (256-byte rows) starting at `tile_base`
+// (wave-uniform).  The LDS-DMA instruction goes through inline asm on purpose: the compiler
+// then does not track it and puts no vmcnt wait in front of LDS reads of the other stage;
+// completion is enforced by wait_async_loads() + barrier before a stage is read.
+// rows_avail < 64: rows past the end are replaced by the last valid row (finite data; such
+// keys are masked by the caller).
 template <bool KFMT>
-__device__ inline void load_tile_async(const unsigned char* gbase, int row0, int max_row,
-                                       LDS_PTR(unsigned char) dst, int wave, int lane) {
+__device__ inline void load_tile_async(const LaneCtx& lc, const unsigned char* tile_base, int rows_avail,
+                                       unsigned lds_stage /* LDS byte address of the destination tile */) {
+  const unsigned voff = KFMT ? lc.dma_k : lc.dma_v;
+  const unsigned m0_0 = __builtin_amdgcn_readfirstlane(lds_stage + lc.wave * 1024);
+  if (rows_avail >= kTile) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int wl = wave * 4 + i;                 // which KB of the tile this wave fills
-    const int r = wl * 4 + (lane >> 4);          // tile row
-    const int pos = lane & 15;                   // 16-byte slot inside the LDS row
-    const int chunk = KFMT ? (pos ^ (r & 15)) : ((((pos >> 1) ^ (r & 7)) << 1) | (pos & 1));
-    const int grow = min(row0 + r, max_row);
-    const unsigned char* src = gbase + (size_t)grow * ROWB + chunk * 16;
-    const unsigned int lds_addr =
-        __builtin_amdgcn_readfirstlane((unsigned int)(unsigned long long)(dst + wl * 1024));
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
-                 :
-                 : "s"(lds_addr), "v"(src)
-                 : "memory", "m0");
+    for (int i = 0; i < 4; ++i) {
+      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+                   :
+                   : "s"(m0_0 + i * 4096), "v"(voff), "s"(tile_base + i * 4096)
+                   : "memory", "m0");
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int r = lc.dma_r0 + 16 * i;
+      const int back = max(r - (rows_avail - 1), 0);                    // rows to step back
+      const unsigned char* src = tile_base + i * 4096 + (long long)voff - (long long)back * ROWB;
+      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+                   :
+                   : "s"(m0_0 + i * 4096), "v"(src)
+                   : "memory", "m0");
+    }
   }
 }
 
+// The staging area is 1 KB aligned, so flipping address bits 5..7 stays inside a row.
+__device__ inline LDS_PTR(const unsigned char) xor_ptr(LDS_PTR(const unsigned char) p, unsigned bits) {
+  return (LDS_PTR(const unsigned char))(unsigned long long)((unsigned)(unsigned long long)p ^ bits);
+}
+
+// s_waitcnt vmcnt(0) with the other counters left alone (gfx9 encoding).
+__device__ inline void wait_async_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
 // One staged 64-key tile folded into the wave's state.
-//   kA (and kB when TAIL: hi, lo parts): K-format tiles; vS: V-format tile.
+//   KOFF / KOFF2 / VOFF: compile-time LDS offsets of the K tile (hi), the lo tile (TAIL) and
+//   the V tile relative to the stage origin the LaneCtx pointers refer to.
 //   bias (TAIL only): 64 floats in LDS: log2 B_j, or -inf for masked / absent columns.
-//   nvalid: valid keys of the tile (Phase 1; keys >= nvalid are masked).
-template <bool TAIL>
-__device__ inline void absorb_tile(State& st, const bf16x8 (&qreg)[8], LDS_PTR(const unsigned char) kA,
-                                   LDS_PTR(const unsigned char) kB, LDS_PTR(const unsigned char) vS,
-                                   LDS_PTR(const float) bias, int nvalid, float c, int lane) {
-  const int lam = lane & 31, h = lane >> 5;
+//   RAGGED: keys >= nvalid contribute nothing (their staged rows hold finite filler).
+template <bool TAIL, bool RAGGED, int KOFF, int KOFF2, int VOFF>
+__device__ inline void absorb_tile(State& st, const bf16x8 (&qreg)[8], const LaneCtx& lc,
+                                   LDS_PTR(const float) bias, int nvalid, float c) {
+  const int h = lc.h;
   f32x16 s0 = {0}, s1 = {0};
-  {
-    const int rowoff = lam * ROWB;
-    const int sw = lam & 15;
-    constexpr int NK = TAIL ? 16 : 8;              // TAIL: hi chain then lo chain
-    auto kread = [&](int i, bf16x8& a0, bf16x8& a1) {
-      LDS_PTR(const unsigned char) base = (TAIL && i >= 8) ? kB : kA;
-      const int off = rowoff + (((2 * (i & 7) + h) ^ sw) << 4);
-      a0 = *reinterpret_cast<LDS_PTR(const bf16x8)>(base + off);
-      a1 = *reinterpret_cast<LDS_PTR(const bf16x8)>(base + off + 32 * ROWB);
-    };
-    bf16x8 ka[3][2];
-    kread(0, ka[0][0], ka[0][1]);
-    kread(1, ka[1][0], ka[1][1]);
 #pragma unroll
-    for (int i = 0; i < NK; ++i) {
-      if (i + 2 < NK) kread(i + 2, ka[(i + 2) % 3][0], ka[(i + 2) % 3][1]);
-      s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[i % 3][0], qreg[i & 7], s0, 0, 0, 0);
-      s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[i % 3][1], qreg[i & 7], s1, 0, 0, 0);
+  for (int ks = 0; ks < 8; ++ks) {
+    LDS_PTR(const unsigned char) kp = xor_ptr(lc.kbase, ks << 5);
+    const bf16x8 a0 = *reinterpret_cast<LDS_PTR(const bf16x8)>(kp + KOFF);
+    const bf16x8 a1 = *reinterpret_cast<LDS_PTR(const bf16x8)>(kp + KOFF + 32 * ROWB);
+    s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qreg[ks], s0, 0, 0, 0);
+    s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qreg[ks], s1, 0, 0, 0);
+  }
+  if (TAIL) {
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      LDS_PTR(const unsigned char) kp = xor_ptr(lc.kbase, ks << 5);
+      const bf16x8 a0 = *reinterpret_cast<LDS_PTR(const bf16x8)>(kp + KOFF2);
+      const bf16x8 a1 = *reinterpret_cast<LDS_PTR(const bf16x8)>(kp + KOFF2 + 32 * ROWB);
+      s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qreg[ks], s0, 0, 0, 0);
+      s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qreg[ks], s1, 0, 0, 0);
     }
   }
-  // ---- logits in the log2 domain; register r of half kk <-> key 32 kk + (r/4)*8 + 4h + r%4 ----
+  // ---- softmax in the log2 domain; register r of half kk <-> key 32 kk + (r/4)*8 + 4h + r%4 ----
   float x[32];
+  float tmax;
   if (TAIL) {
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk)
@@ -222,23 +251,19 @@ __device__ inline void absorb_tile(State& st, const bf16x8 (&qreg)[8], LDS_PTR(c
         x[16 * kk + 4 * g + 2] = fmaf(s[4 * g + 2], c, b.z);
         x[16 * kk + 4 * g + 3] = fmaf(s[4 * g + 3], c, b.w);
       }
+    tmax = x[0];
+#pragma unroll
+    for (int r = 1; r < 32; ++r) tmax = fmaxf(tmax, x[r]);
   } else {
+    // max over the raw accumulators (the scale is positive); filler keys of a ragged tile
+    // may take part in the max: any bound >= the valid logits keeps the softmax exact.
+    float t = s0[0];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      x[r] = s0[r] * c;
-      x[16 + r] = s1[r] * c;
-    }
-    if (nvalid < kTile) {
+    for (int r = 1; r < 16; ++r) t = fmaxf(t, s0[r]);
 #pragma unroll
-      for (int r = 0; r < 32; ++r) {
-        const int key = 32 * (r >> 4) + ((r & 15) / 4) * 8 + 4 * h + (r % 4);
-        if (key >= nvalid) x[r] = -INFINITY;
-      }
-    }
+    for (int r = 0; r < 16; ++r) t = fmaxf(t, s1[r]);
+    tmax = t * c;
   }
-  float tmax = x[0];
-#pragma unroll
-  for (int r = 1; r < 32; ++r) tmax = fmaxf(tmax, x[r]);
   tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
   const float m_new = fmaxf(st.m, tmax);
   const float m_safe = m_new == -INFINITY ? 0.f : m_new;
@@ -251,20 +276,34 @@ __device__ inline void absorb_tile(State& st, const bf16x8 (&qreg)[8], LDS_PTR(c
     st.m = m_new;
   }
   float psum = 0.f;
+  if (TAIL) {
 #pragma unroll
-  for (int r = 0; r < 32; ++r) {
-    x[r] = __builtin_amdgcn_exp2f(x[r] - m_safe);
-    psum += x[r];
+    for (int r = 0; r < 32; ++r) {
+      x[r] = __builtin_amdgcn_exp2f(x[r] - m_safe);
+      psum += x[r];
+    }
+  } else {
+    const float nm = -m_safe;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      x[r] = __builtin_amdgcn_exp2f(fmaf(s0[r], c, nm));
+      x[16 + r] = __builtin_amdgcn_exp2f(fmaf(s1[r], c, nm));
+    }
+    if (RAGGED) {
+#pragma unroll
+      for (int r = 0; r < 32; ++r) {
+        const int key = 32 * (r >> 4) + ((r & 15) / 4) * 8 + 4 * h + (r % 4);
+        if (key >= nvalid) x[r] = 0.f;
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < 32; ++r) psum += x[r];
   }
   st.l += psum;
   if (TAIL) st.l_tail += psum;
   // ---- O^T += V^T P^T: four contraction steps of 16 keys ----
-  // Transposed LDS read: lane j of a 16-lane group points at 4 channels of key (j >> 2);
-  // it receives channel (group base + j) of the group's four keys.
-  const int j16 = lane & 15;
-  const int kq = 4 * h + (j16 >> 2);                 // key offset of this lane's pointer, = key & 7
-  const int vlane = kq * ROWB + 8 * (j16 & 3);
-  const int lhalf = (lane >> 4) & 1;
+  // Transposed LDS read: lane j of a 16-lane group points at 4 channels of key (j >> 2) and
+  // receives channel (group base + j) of the group's four keys.
 #pragma unroll
   for (int step = 0; step < 4; ++step) {            // keys 16 step .. 16 step + 15
     u32x4 pw;
@@ -273,11 +312,10 @@ __device__ inline void absorb_tile(State& st, const bf16x8 (&qreg)[8], LDS_PTR(c
     const bf16x8 pb = __builtin_bit_cast(bf16x8, pw);
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt) {
-      const int off = 16 * step * ROWB + vlane + (((2 * dt + lhalf) ^ kq) << 5);
-      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-          reinterpret_cast<LDS_PTR(s16x4)>(const_cast<LDS_PTR(unsigned char)>(vS + off)));
-      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-          reinterpret_cast<LDS_PTR(s16x4)>(const_cast<LDS_PTR(unsigned char)>(vS + off + 8 * ROWB)));
+      LDS_PTR(unsigned char) vp =
+          const_cast<LDS_PTR(unsigned char)>(xor_ptr(lc.vbase, dt << 6)) + VOFF + 16 * step * ROWB;
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<LDS_PTR(s16x4)>(vp));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<LDS_PTR(s16x4)>(vp + 8 * ROWB));
       const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
       const u32x4 aw = {l2.x, l2.y, h2.x, h2.y};
       st.ot[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, aw), pb,
@@ -285,9 +323,6 @@ __device__ inline void absorb_tile(State& st, const bf16x8 (&qreg)[8], LDS_PTR(c
     }
   }
 }
-
-// s_waitcnt vmcnt(0) with the other counters left alone (gfx9 encoding).
-__device__ inline void wait_async_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
 template <bool DENSE>
 __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
@@ -314,6 +349,23 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
   const int qb = tpb == 1 ? (wave >> 1) : 0;         // which of the workgroup's query blocks
   const float c = p.scale * 1.44269504088896340736f;
   LDS_PTR(unsigned char) lds = (LDS_PTR(unsigned char)) & stage[0][0];
+  const unsigned lds_addr = (unsigned)(unsigned long long)lds;
+
+  LaneCtx lc;
+  lc.h = h;
+  lc.wave = __builtin_amdgcn_readfirstlane(wave);
+  {
+    const int r = 4 * wave + (lane >> 4);        // tile row of this lane's first DMA load
+    const int pos = lane & 15;                   // 16-byte slot inside the LDS row
+    lc.dma_r0 = r;
+    lc.dma_k = r * ROWB + ((pos ^ (r & 15)) << 4);
+    lc.dma_v = r * ROWB + (((((pos >> 1) ^ (r & 7)) << 1) | (pos & 1)) << 4);
+    const int j16 = lane & 15;
+    const int kq = 4 * h + (j16 >> 2);           // key offset of this lane's V pointer (= key & 7)
+    const int lhalf = (lane >> 4) & 1;
+    lc.kbase = lds + lam * ROWB + (((lam & 15) ^ h) << 4);
+    lc.vbase = lds + kq * ROWB + 8 * (j16 & 3) + ((lhalf ^ kq) << 5);
+  }
 
   // ---- Q^T operand: this lane's query row, 8 channel slices of 16 ----
   const int q_row = sg * QROWS + 32 * wave + lam;
@@ -355,7 +407,8 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
   }
 
   // ---- Phase 1: walk the exact tiles (all tiles; or the union of the selected blocks) ----
-  const int n_tiles = (L + kTile - 1) / kTile;
+  // The main loop takes full tiles only; a ragged last tile is folded in afterwards.
+  const int n_tiles = L / kTile;
   int w_word = -1, pend = -1, pend_in = 0, dense_t = 0;
   unsigned int w_union = 0u, w_m0 = 0u, w_m1 = 0u;
   auto next_tile = [&](int& tile, int& inmask) -> bool {
@@ -373,52 +426,70 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
     }
     while (w_union == 0u) {
       if (++w_word >= nwords) return false;
-      w_m0 = chosen[0][w_word];
-      w_m1 = chosen[1][w_word];
-      w_union = __builtin_amdgcn_readfirstlane(w_m0 | w_m1);
+      w_m0 = __builtin_amdgcn_readfirstlane(chosen[0][w_word]);
+      w_m1 = __builtin_amdgcn_readfirstlane(chosen[1][w_word]);
+      w_union = w_m0 | w_m1;
     }
     const int b = __builtin_ctz(w_union);
     w_union &= w_union - 1u;
     const int j = w_word * 32 + b;
-    inmask = __builtin_amdgcn_readfirstlane(((w_m0 >> b) & 1u) | (((w_m1 >> b) & 1u) << 1));
+    inmask = ((w_m0 >> b) & 1u) | (((w_m1 >> b) & 1u) << 1);
     if (tpb == 1) {
       tile = j;
+      if (tile >= n_tiles) return false;       // only the ragged tile is left
     } else {
       tile = 2 * j;
-      inmask = inmask ? 3 : 0;
-      if ((2 * j + 1) * kTile < L) {
+      inmask = 3;
+      if (tile >= n_tiles) return false;
+      if (2 * j + 1 < n_tiles) {
         pend = 2 * j + 1;
-        pend_in = inmask;
+        pend_in = 3;
       }
     }
     return true;
   };
+  auto issue_kv = [&](int tile, int buf) {
+    const int rows_avail = L - tile * kTile;
+    load_tile_async<true>(lc, kg + (size_t)tile * TILEB, rows_avail, lds_addr + buf * 2 * TILEB);
+    load_tile_async<false>(lc, vg + (size_t)tile * TILEB, rows_avail, lds_addr + buf * 2 * TILEB + TILEB);
+  };
 
   int tile_cur = 0, in_cur = 0, tile_nxt = 0, in_nxt = 0;
   bool have = next_tile(tile_cur, in_cur);
-  if (have) {
-    load_tile_async<true>(kg, tile_cur * kTile, L - 1, lds, wave, lane);
-    load_tile_async<false>(vg, tile_cur * kTile, L - 1, lds + TILEB, wave, lane);
-  }
-  int buf = 0;
-  while (have) {
+  if (have) issue_kv(tile_cur, 0);
+  // Two tiles per trip so that the stage index is a compile-time constant.
+  auto half_trip = [&](auto buf_tag) {
+    constexpr int BUF = decltype(buf_tag)::value;
     const bool have_nxt = next_tile(tile_nxt, in_nxt);
     wait_async_loads();
-    __syncthreads();   // tile `cur` is complete in stage[buf]; stage[buf^1] is no longer read
-    if (have_nxt) {
-      LDS_PTR(unsigned char) dst = lds + (buf ^ 1) * 2 * TILEB;
-      load_tile_async<true>(kg, tile_nxt * kTile, L - 1, dst, wave, lane);
-      load_tile_async<false>(vg, tile_nxt * kTile, L - 1, dst + TILEB, wave, lane);
-    }
-    if ((in_cur >> qb) & 1) {
-      LDS_PTR(const unsigned char) kS = lds + buf * 2 * TILEB;
-      const int nvalid = min(kTile, L - tile_cur * kTile);
-      absorb_tile<false>(st, qreg, kS, kS, kS + TILEB, nullptr, nvalid, c, lane);
-    }
+    __syncthreads();   // tile `cur` is complete in stage[BUF]; stage[BUF^1] is no longer read
+    if (have_nxt) issue_kv(tile_nxt, BUF ^ 1);
+    if ((in_cur >> qb) & 1)
+      absorb_tile<false, false, BUF * 2 * TILEB, 0, BUF * 2 * TILEB + TILEB>(st, qreg, lc, nullptr, kTile, c);
     tile_cur = tile_nxt;
     in_cur = in_nxt;
     have = have_nxt;
-    buf ^= 1;
+  };
+  while (have) {
+    half_trip(std::integral_constant<int, 0>{});
+    if (!have) break;
+    half_trip(std::integral_constant<int, 1>{});
+  }
+
+  // ---- ragged last tile (L not a multiple of 64), if this workgroup attends it ----
+  if (L % kTile != 0) {
+    const int tile = n_tiles, jb = tile / tpb;
+    const unsigned inm = DENSE ? 3u
+                               : (((chosen[0][jb >> 5] >> (jb & 31)) & 1u) |
+                                  (tpb == 1 ? (((chosen[1][jb >> 5] >> (jb & 31)) & 1u) << 1) : 0u));
+    if (inm) {            // uniform over the workgroup
+      __syncthreads();
+      issue_kv(tile, 0);
+      wait_async_loads();
+      __syncthreads();
+      if ((inm >> qb) & 1)
+        absorb_tile<false, true, 0, 0, TILEB>(st, qreg, lc, nullptr, L - tile * kTile, c);
+    }
   }
 
   // ---- Phase 2: centroid tiles (hi, lo, values) ----
@@ -430,17 +501,18 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
     LDS_PTR(const float) my_bias = (LDS_PTR(const float)) & bias_s[qb][0];
     for (int g0 = 0; g0 < N; g0 += kTile) {
       __syncthreads();                         // previous tile fully consumed
-      load_tile_async<true>(khg, g0, p.npad - 1, lds, wave, lane);
-      load_tile_async<true>(klg, g0, p.npad - 1, lds + TILEB, wave, lane);
-      load_tile_async<false>(vbg, g0, p.npad - 1, lds + 2 * TILEB, wave, lane);
+      load_tile_async<true>(lc, khg + (size_t)g0 * ROWB, kTile, lds_addr);
+      load_tile_async<true>(lc, klg + (size_t)g0 * ROWB, kTile, lds_addr + TILEB);
+      load_tile_async<false>(lc, vbg + (size_t)g0 * ROWB, kTile, lds_addr + 2 * TILEB);
       if (tid < 2 * kTile) {
         const int b = tid >> 6, j = g0 + (tid & 63);
-        const bool masked = tpb == 2 && b == 1 ? true : ((chosen[b][(j >> 5) & (MASK_WORDS - 1)] >> (j & 31)) & 1u);
+        const bool masked =
+            (tpb == 2 && b == 1) ? true : ((chosen[b][(j >> 5) & (MASK_WORDS - 1)] >> (j & 31)) & 1u);
         bias_s[b][tid & 63] = masked ? -INFINITY : p.bias[j];
       }
       wait_async_loads();
       __syncthreads();
-      absorb_tile<true>(st, qreg, lds, lds + TILEB, lds + 2 * TILEB, my_bias, kTile, c, lane);
+      absorb_tile<true, false, 0, TILEB, 2 * TILEB>(st, qreg, lc, my_bias, kTile, c);
     }
   }
 
