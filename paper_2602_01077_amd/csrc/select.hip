@@ -129,15 +129,28 @@ __global__ __launch_bounds__(256) void topk_kernel(const double* __restrict__ z,
       if ((key & himask) == prefix) atomicAdd(&hist[(int)((key >> shift) & 0xff)], 1);
     }
     __syncthreads();
-    if (tid == 0) {
-      int want = s_want, digit = 255;
-      for (; digit > 0; --digit) {
-        const int c = hist[digit];
-        if (c >= want) break;
-        want -= c;
+    // Wave 0 walks the 256 bins from the top: lane l owns bins 255-4l .. 252-4l, a wave
+    // prefix sum over the per-lane totals finds the lane, then the lane finds its bin.
+    if (tid < 64) {
+      const int want = s_want;
+      const int b0 = 255 - 4 * tid;
+      const int c0 = hist[b0], c1 = hist[b0 - 1], c2 = hist[b0 - 2], c3 = hist[b0 - 3];
+      const int mine = c0 + c1 + c2 + c3;
+      int incl = mine;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const int up = __shfl_up(incl, off);
+        if (tid >= off) incl += up;
       }
-      s_want = want;
-      s_prefix = prefix | ((unsigned long long)digit << shift);
+      const int before = incl - mine;               // keys in bins above this lane's bins
+      if (before < want && want <= incl) {          // exactly one lane
+        int w = want - before, digit = b0;
+        if (w > c0) { w -= c0; digit = b0 - 1;
+          if (w > c1) { w -= c1; digit = b0 - 2;
+            if (w > c2) { w -= c2; digit = b0 - 3; } } }
+        s_want = w;
+        s_prefix = prefix | ((unsigned long long)digit << shift);
+      }
     }
     __syncthreads();
   }

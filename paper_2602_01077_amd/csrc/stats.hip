@@ -136,6 +136,11 @@ __global__ __launch_bounds__(256) void reduce_h_kernel(const float* __restrict__
 
 }  // namespace
 
+hipError_t launch_block_stats_bf16_b64(const Dims& dm, const void* q, const void* k, const void* v,
+                                       float* qbar, float* kbar, float* vsum,
+                                       double* qbar64, double* kbar64, float* partial_h,
+                                       const StatsPlan& plan, hipStream_t stream);
+
 hipError_t launch_block_stats(const Dims& dm, const void* q, const void* k, const void* v,
                               float* qbar, float* kbar, float* vsum, float* hsum,
                               double* qbar64, double* kbar64, float* partial_h,
@@ -146,7 +151,11 @@ hipError_t launch_block_stats(const Dims& dm, const void* q, const void* k, cons
   hipLaunchKernelGGL((stats_kernel<T, DD>), grid, dim3(256), 0, stream, (const T*)q, (const T*)k, \
                      (const T*)v, qbar, kbar, vsum, qbar64, kbar64, partial_h, dm.L, dm.B, dm.N,   \
                      plan.chunk_blocks, plan.n_chunks)
-  if (dm.dtype == PISA_BF16) {
+  if (dm.dtype == PISA_BF16 && dm.B == kTile) {
+    hipError_t e = launch_block_stats_bf16_b64(dm, q, k, v, qbar, kbar, vsum, qbar64, kbar64,
+                                               partial_h, plan, stream);
+    if (e != hipSuccess) return e;
+  } else if (dm.dtype == PISA_BF16) {
     PISA_STATS(__hip_bfloat16, 128);
   } else if (dm.d == 64) {
     PISA_STATS(float, 64);

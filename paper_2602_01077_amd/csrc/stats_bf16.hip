@@ -1,0 +1,190 @@
+// pisa_block_stats for bf16 inputs, head_dim 128, block 64: one streaming pass (Alg. 1 line 1).
+//
+// Grid (n_chunks, batch*heads); a workgroup of 4 waves walks `chunk_blocks` consecutive
+// 64-token blocks of one head.  Per block:
+//   * wave w loads rows 16w..16w+15 of the Q, K and V tiles, one 4-byte channel pair per
+//     lane (a wave-load is one 256-byte row), and adds them in fp64 (exact for bf16 data);
+//     the four waves' partial column sums meet in LDS and are added in wave order;
+//   * K is centred on the block mean in registers, split into bf16 hi + lo parts and
+//     written to LDS together with V (rows swizzled for conflict-free transposed reads);
+//   * H += Kc^T V on the matrix cores: wave w owns the 32 key channels 32w..32w+31 and all
+//     128 value channels (four 32x32 accumulators); both operands are contracted over
+//     tokens, so both come from ds_read_b64_tr_b16.
+// The partial H of the chunk goes to scratch; partials are added in chunk order by the
+// caller's reduction kernel, so hsum is run-to-run identical.
+#include "common.h"
+
+namespace pisa {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef double f64x2 __attribute__((ext_vector_type(2)));
+#define LDS_PTR(T) __attribute__((address_space(3))) T*
+
+constexpr int D = 128;
+constexpr int ROWB = 256;
+constexpr int TILEB = kTile * ROWB;
+
+__device__ inline unsigned int pack_bf16(float lo, float hi) {
+  f32x2 f = {lo, hi};
+  bf16x2 b = __builtin_convertvector(f, bf16x2);
+  return __builtin_bit_cast(unsigned int, b);
+}
+
+// Byte address of channel pair `c2` (channels 2 c2, 2 c2 + 1) of row n in a swizzled tile:
+// 32-byte chunks are XORed with (n & 7).
+__device__ inline int swz_pair(int n, int c2) {
+  const int byte = c2 * 4;
+  return n * ROWB + ((((byte >> 5) ^ (n & 7)) << 5) | (byte & 31));
+}
+
+// A / B operand of v_mfma_f32_32x32x16_bf16 for contraction step `step` (16 tokens) and
+// channel tile `ct` (32 channels), read transposed from a swizzled [token][channel] tile.
+__device__ inline bf16x8 read_operand(LDS_PTR(const unsigned char) tile, int lane, int step, int ct) {
+  const int j16 = lane & 15, h = lane >> 5, lhalf = (lane >> 4) & 1;
+  const int kq = 4 * h + (j16 >> 2);
+  const int off = (16 * step + kq) * ROWB + 8 * (j16 & 3) + (((2 * ct + lhalf) ^ kq) << 5);
+  LDS_PTR(unsigned char) p = const_cast<LDS_PTR(unsigned char)>(tile) + off;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<LDS_PTR(s16x4)>(p));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<LDS_PTR(s16x4)>(p + 8 * ROWB));
+  const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
+  const u32x4 w = {l2.x, l2.y, h2.x, h2.y};
+  return __builtin_bit_cast(bf16x8, w);
+}
+
+__global__ __launch_bounds__(256, 2) void stats_bf16_kernel(
+    const unsigned int* __restrict__ q, const unsigned int* __restrict__ k, const unsigned int* __restrict__ v,
+    float* __restrict__ qbar, float* __restrict__ kbar, float* __restrict__ vsum,
+    double* __restrict__ qbar64, double* __restrict__ kbar64, float* __restrict__ partial_h,
+    int L, int N, int chunk_blocks, int n_chunks) {
+  __shared__ __attribute__((aligned(1024))) unsigned char khi_s[TILEB];
+  __shared__ __attribute__((aligned(1024))) unsigned char klo_s[TILEB];
+  __shared__ __attribute__((aligned(1024))) unsigned char v_s[TILEB];
+  __shared__ __attribute__((aligned(16))) double red[3][4][D];
+  __shared__ float kmean_s[D];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int chunk = blockIdx.x;
+  const size_t bh = blockIdx.y;
+  const size_t head_words = (size_t)L * (D / 2);
+  const unsigned int* qh = q + bh * head_words;
+  const unsigned int* kh = k + bh * head_words;
+  const unsigned int* vh = v + bh * head_words;
+  LDS_PTR(unsigned char) khi = (LDS_PTR(unsigned char))khi_s;
+  LDS_PTR(unsigned char) klo = (LDS_PTR(unsigned char))klo_s;
+  LDS_PTR(unsigned char) vt = (LDS_PTR(unsigned char))v_s;
+
+  f32x16 acc[4];
+#pragma unroll
+  for (int bt = 0; bt < 4; ++bt) acc[bt] = (f32x16){0};
+
+  const int j_begin = chunk * chunk_blocks;
+  const int j_end = min(N, j_begin + chunk_blocks);
+  for (int j = j_begin; j < j_end; ++j) {
+    const int row0 = j * kTile;
+    const int rows = min(kTile, L - row0);
+    // ---- load this wave's 16 rows, one channel pair per lane ----
+    unsigned int kx[16], vx[16], qx[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int n = 16 * wave + i;
+      kx[i] = vx[i] = qx[i] = 0u;
+      if (n < rows) {
+        const size_t o = (size_t)(row0 + n) * (D / 2) + lane;
+        qx[i] = qh[o];
+        kx[i] = kh[o];
+        vx[i] = vh[o];
+      }
+    }
+    // ---- fp64 column sums of the 16 rows (zeros of absent rows add nothing) ----
+    double sq0 = 0, sq1 = 0, sk0 = 0, sk1 = 0, sv0 = 0, sv1 = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      sq0 += (double)__uint_as_float(qx[i] << 16);
+      sq1 += (double)__uint_as_float(qx[i] & 0xffff0000u);
+      sk0 += (double)__uint_as_float(kx[i] << 16);
+      sk1 += (double)__uint_as_float(kx[i] & 0xffff0000u);
+      sv0 += (double)__uint_as_float(vx[i] << 16);
+      sv1 += (double)__uint_as_float(vx[i] & 0xffff0000u);
+    }
+    *reinterpret_cast<f64x2*>(&red[0][wave][2 * lane]) = (f64x2){sq0, sq1};
+    *reinterpret_cast<f64x2*>(&red[1][wave][2 * lane]) = (f64x2){sk0, sk1};
+    *reinterpret_cast<f64x2*>(&red[2][wave][2 * lane]) = (f64x2){sv0, sv1};
+    __syncthreads();
+    if (tid < D) {
+      const double sq = ((red[0][0][tid] + red[0][1][tid]) + red[0][2][tid]) + red[0][3][tid];
+      const double sk = ((red[1][0][tid] + red[1][1][tid]) + red[1][2][tid]) + red[1][3][tid];
+      const double sv = ((red[2][0][tid] + red[2][1][tid]) + red[2][2][tid]) + red[2][3][tid];
+      const double qm = sq / (double)rows, km = sk / (double)rows;
+      const size_t o = (bh * N + j) * D + tid;
+      qbar[o] = (float)qm;
+      kbar[o] = (float)km;
+      vsum[o] = (float)sv;
+      qbar64[o] = qm;
+      kbar64[o] = km;
+      kmean_s[tid] = (float)km;
+    }
+    __syncthreads();
+    // ---- centre K, split hi/lo, stage with V ----
+    {
+      const float m0 = kmean_s[2 * lane], m1 = kmean_s[2 * lane + 1];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int n = 16 * wave + i;
+        unsigned int hi = 0u, lo = 0u;
+        if (n < rows) {
+          const float c0 = __uint_as_float(kx[i] << 16) - m0;
+          const float c1 = __uint_as_float(kx[i] & 0xffff0000u) - m1;
+          hi = pack_bf16(c0, c1);
+          lo = pack_bf16(c0 - __uint_as_float(hi << 16), c1 - __uint_as_float(hi & 0xffff0000u));
+        }
+        const int a = swz_pair(n, lane);
+        *reinterpret_cast<LDS_PTR(unsigned int)>(khi + a) = hi;
+        *reinterpret_cast<LDS_PTR(unsigned int)>(klo + a) = lo;
+        *reinterpret_cast<LDS_PTR(unsigned int)>(vt + a) = vx[i];
+      }
+    }
+    __syncthreads();
+    // ---- H[32 wave .. +32][all 128] += Kc^T V over the 64 tokens ----
+#pragma unroll
+    for (int step = 0; step < 4; ++step) {
+      const bf16x8 ahi = read_operand(khi, lane, step, wave);
+      const bf16x8 alo = read_operand(klo, lane, step, wave);
+#pragma unroll
+      for (int bt = 0; bt < 4; ++bt) {
+        const bf16x8 b = read_operand(vt, lane, step, bt);
+        acc[bt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ahi, b, acc[bt], 0, 0, 0);
+        acc[bt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(alo, b, acc[bt], 0, 0, 0);
+      }
+    }
+    // the next block's LDS writes are separated from these reads by its two barriers
+  }
+  // acc[bt][r] = H[32 wave + (r/4)*8 + 4h + r%4][32 bt + lam]
+  float* ph = partial_h + (bh * n_chunks + chunk) * (size_t)D * D;
+  const int lam = lane & 31, h = lane >> 5;
+#pragma unroll
+  for (int bt = 0; bt < 4; ++bt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      ph[(size_t)(32 * wave + (r / 4) * 8 + 4 * h + (r % 4)) * D + 32 * bt + lam] = acc[bt][r];
+}
+
+}  // namespace
+
+hipError_t launch_block_stats_bf16_b64(const Dims& dm, const void* q, const void* k, const void* v,
+                                       float* qbar, float* kbar, float* vsum,
+                                       double* qbar64, double* kbar64, float* partial_h,
+                                       const StatsPlan& plan, hipStream_t stream) {
+  hipLaunchKernelGGL(stats_bf16_kernel, dim3(plan.n_chunks, dm.bh()), dim3(256), 0, stream,
+                     (const unsigned int*)q, (const unsigned int*)k, (const unsigned int*)v, qbar, kbar,
+                     vsum, qbar64, kbar64, partial_h, dm.L, dm.N, plan.chunk_blocks, plan.n_chunks);
+  return hipGetLastError();
+}
+
+}  // namespace pisa
