@@ -18,7 +18,7 @@
 // 1 KB of consecutive LDS, so bank conflicts are avoided by permuting which global chunk
 // each lane fetches: K rows XOR their 16-byte chunk index with (row & 15) (conflict-free
 // ds_read_b128 of one chunk from 16 different rows); V rows XOR their 32-byte chunk index
-// with (row & 7) (conflict-free ds_read_b64_tr_b16, which hands a 16-lane group a
+// with a 3-bit function of the row (conflict-free ds_read_b64_tr_b16, which hands a 16-lane group a
 // 16-channel x 4-key transposed fragment, i.e. the V^T operand straight from row-major V).
 //
 // PISA, block 64: the two query blocks of a workgroup walk the UNION of their selected
@@ -200,6 +200,12 @@ __device__ inline void load_tile_async(const LaneCtx& lc, const unsigned char* t
   }
 }
 
+// V-format swizzle: the 32-byte chunk index of row r is XORed with this 3-bit value.  The
+// four consecutive rows a 16-lane group reads together get 0,2,4,6 (or 1,3,5,7), so the two
+// groups of a half-wave (chunk indices differing in bit 0) hit disjoint banks: measured
+// 2.2 clk per ds_read_b64_tr_b16 against 4.2 clk with a plain (r & 7) XOR.
+__device__ inline int vswz(int r) { return ((r & 3) << 1) | ((r >> 2) & 1); }
+
 // The staging area is 1 KB aligned, so flipping address bits 5..7 stays inside a row.
 __device__ inline LDS_PTR(const unsigned char) xor_ptr(LDS_PTR(const unsigned char) p, unsigned bits) {
   return (LDS_PTR(const unsigned char))(unsigned long long)((unsigned)(unsigned long long)p ^ bits);
@@ -359,12 +365,12 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
     const int pos = lane & 15;                   // 16-byte slot inside the LDS row
     lc.dma_r0 = r;
     lc.dma_k = r * ROWB + ((pos ^ (r & 15)) << 4);
-    lc.dma_v = r * ROWB + (((((pos >> 1) ^ (r & 7)) << 1) | (pos & 1)) << 4);
+    lc.dma_v = r * ROWB + (((((pos >> 1) ^ vswz(r)) << 1) | (pos & 1)) << 4);
     const int j16 = lane & 15;
     const int kq = 4 * h + (j16 >> 2);           // key offset of this lane's V pointer (= key & 7)
     const int lhalf = (lane >> 4) & 1;
     lc.kbase = lds + lam * ROWB + (((lam & 15) ^ h) << 4);
-    lc.vbase = lds + kq * ROWB + 8 * (j16 & 3) + ((lhalf ^ kq) << 5);
+    lc.vbase = lds + kq * ROWB + 8 * (j16 & 3) + ((lhalf ^ vswz(kq)) << 5);
   }
 
   // ---- Q^T operand: this lane's query row, 8 channel slices of 16 ----

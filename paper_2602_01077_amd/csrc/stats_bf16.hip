@@ -37,11 +37,14 @@ __device__ inline unsigned int pack_bf16(float lo, float hi) {
   return __builtin_bit_cast(unsigned int, b);
 }
 
-// Byte address of channel pair `c2` (channels 2 c2, 2 c2 + 1) of row n in a swizzled tile:
-// 32-byte chunks are XORed with (n & 7).
+// Swizzle of a staged [token][channel] tile: the 32-byte chunk index of row n is XORed with
+// this 3-bit value, which makes the transposed reads below bank-conflict free.
+__device__ inline int swz3(int n) { return ((n & 3) << 1) | ((n >> 2) & 1); }
+
+// Byte address of channel pair `c2` (channels 2 c2, 2 c2 + 1) of row n in a swizzled tile.
 __device__ inline int swz_pair(int n, int c2) {
   const int byte = c2 * 4;
-  return n * ROWB + ((((byte >> 5) ^ (n & 7)) << 5) | (byte & 31));
+  return n * ROWB + ((((byte >> 5) ^ swz3(n)) << 5) | (byte & 31));
 }
 
 // A / B operand of v_mfma_f32_32x32x16_bf16 for contraction step `step` (16 tokens) and
@@ -49,7 +52,7 @@ __device__ inline int swz_pair(int n, int c2) {
 __device__ inline bf16x8 read_operand(LDS_PTR(const unsigned char) tile, int lane, int step, int ct) {
   const int j16 = lane & 15, h = lane >> 5, lhalf = (lane >> 4) & 1;
   const int kq = 4 * h + (j16 >> 2);
-  const int off = (16 * step + kq) * ROWB + 8 * (j16 & 3) + (((2 * ct + lhalf) ^ kq) << 5);
+  const int off = (16 * step + kq) * ROWB + 8 * (j16 & 3) + (((2 * ct + lhalf) ^ swz3(kq)) << 5);
   LDS_PTR(unsigned char) p = const_cast<LDS_PTR(unsigned char)>(tile) + off;
   const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<LDS_PTR(s16x4)>(p));
   const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<LDS_PTR(s16x4)>(p + 8 * ROWB));
