@@ -214,16 +214,15 @@ __device__ inline LDS_PTR(const unsigned char) xor_ptr(LDS_PTR(const unsigned ch
 // s_waitcnt vmcnt(0) with the other counters left alone (gfx9 encoding).
 __device__ inline void wait_async_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
-// One staged 64-key tile folded into the wave's state.
-//   KOFF / KOFF2 / VOFF: compile-time LDS offsets of the K tile (hi), the lo tile (TAIL) and
-//   the V tile relative to the stage origin the LaneCtx pointers refer to.
-//   bias (TAIL only): 64 floats in LDS: log2 B_j, or -inf for masked / absent columns.
-//   RAGGED: keys >= nvalid contribute nothing (their staged rows hold finite filler).
-template <bool TAIL, bool RAGGED, int KOFF, int KOFF2, int VOFF>
-__device__ inline void absorb_tile(State& st, const bf16x8 (&qreg)[8], const LaneCtx& lc,
-                                   LDS_PTR(const float) bias, int nvalid, float c) {
-  const int h = lc.h;
-  f32x16 s0 = {0}, s1 = {0};
+// ---- the three stages of one 64-key tile ------------------------------------------------
+// LDS offsets (KOFF, KOFF2, VOFF) are compile-time and relative to the staging origin the
+// LaneCtx pointers refer to.
+
+// S^T = K_tile Q^T (TAIL: hi and lo centroid parts accumulate into the same S^T).
+template <bool TAIL, int KOFF, int KOFF2>
+__device__ inline void qk_tile(f32x16& s0, f32x16& s1, const bf16x8 (&qreg)[8], const LaneCtx& lc) {
+  s0 = (f32x16){0};
+  s1 = (f32x16){0};
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks) {
     LDS_PTR(const unsigned char) kp = xor_ptr(lc.kbase, ks << 5);
@@ -242,34 +241,41 @@ __device__ inline void absorb_tile(State& st, const bf16x8 (&qreg)[8], const Lan
       s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qreg[ks], s1, 0, 0, 0);
     }
   }
-  // ---- softmax in the log2 domain; register r of half kk <-> key 32 kk + (r/4)*8 + 4h + r%4 ----
-  float x[32];
+}
+
+// Online softmax in the log2 domain, in two steps so that the only branch (the rescale of O
+// when some row maximum moved) sits in front of the straight-line exponential part.
+// Register r of S^T half kk <-> key 32 kk + (r/4)*8 + 4h + r%4.
+//   bias (TAIL only): 64 floats in LDS: log2 B_j, or -inf for masked / absent columns.
+//   RAGGED: keys >= nvalid contribute nothing (their staged rows hold finite filler).
+
+// Step 1: new running max; rescales l, l_tail and O if it moved.  Returns the (finite)
+// value to subtract.  TAIL: s0, s1 are turned into biased log2-domain logits in place.
+template <bool TAIL>
+__device__ inline float softmax_max(State& st, f32x16& s0, f32x16& s1, const LaneCtx& lc,
+                                    LDS_PTR(const float) bias, float c) {
   float tmax;
   if (TAIL) {
+    const int h = lc.h;
 #pragma unroll
-    for (int kk = 0; kk < 2; ++kk)
+    for (int g = 0; g < 4; ++g) {
+      const f32x4 b0 = *reinterpret_cast<LDS_PTR(const f32x4)>(bias + 8 * g + 4 * h);
+      const f32x4 b1 = *reinterpret_cast<LDS_PTR(const f32x4)>(bias + 32 + 8 * g + 4 * h);
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const f32x4 b = *reinterpret_cast<LDS_PTR(const f32x4)>(bias + 32 * kk + 8 * g + 4 * h);
-        const f32x16& s = kk ? s1 : s0;
-        x[16 * kk + 4 * g + 0] = fmaf(s[4 * g + 0], c, b.x);
-        x[16 * kk + 4 * g + 1] = fmaf(s[4 * g + 1], c, b.y);
-        x[16 * kk + 4 * g + 2] = fmaf(s[4 * g + 2], c, b.z);
-        x[16 * kk + 4 * g + 3] = fmaf(s[4 * g + 3], c, b.w);
+      for (int e = 0; e < 4; ++e) {
+        s0[4 * g + e] = fmaf(s0[4 * g + e], c, b0[e]);
+        s1[4 * g + e] = fmaf(s1[4 * g + e], c, b1[e]);
       }
-    tmax = x[0];
-#pragma unroll
-    for (int r = 1; r < 32; ++r) tmax = fmaxf(tmax, x[r]);
-  } else {
-    // max over the raw accumulators (the scale is positive); filler keys of a ragged tile
-    // may take part in the max: any bound >= the valid logits keeps the softmax exact.
-    float t = s0[0];
-#pragma unroll
-    for (int r = 1; r < 16; ++r) t = fmaxf(t, s0[r]);
-#pragma unroll
-    for (int r = 0; r < 16; ++r) t = fmaxf(t, s1[r]);
-    tmax = t * c;
+    }
   }
+  // max over the accumulators (raw ones when !TAIL: the scale is positive); filler keys of a
+  // ragged tile may take part: any bound >= the valid logits keeps the softmax exact.
+  float t = s0[0];
+#pragma unroll
+  for (int r = 1; r < 16; ++r) t = fmaxf(t, s0[r]);
+#pragma unroll
+  for (int r = 0; r < 16; ++r) t = fmaxf(t, s1[r]);
+  tmax = TAIL ? t : t * c;
   tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
   const float m_new = fmaxf(st.m, tmax);
   const float m_safe = m_new == -INFINITY ? 0.f : m_new;
@@ -281,41 +287,49 @@ __device__ inline void absorb_tile(State& st, const bf16x8 (&qreg)[8], const Lan
     for (int dt = 0; dt < 4; ++dt) st.ot[dt] *= corr;
     st.m = m_new;
   }
-  float psum = 0.f;
-  if (TAIL) {
+  return m_safe;
+}
+
+// Step 2: probabilities, row-sum update, bf16 B operands pb[step] (16 keys each).
+template <bool TAIL, bool RAGGED>
+__device__ inline void softmax_exp(State& st, const f32x16& s0, const f32x16& s1, float m_safe,
+                                   bf16x8 (&pb)[4], const LaneCtx& lc, int nvalid, float c) {
+  float x[32];
+  const float nm = -m_safe;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    x[r] = __builtin_amdgcn_exp2f(TAIL ? s0[r] + nm : fmaf(s0[r], c, nm));
+    x[16 + r] = __builtin_amdgcn_exp2f(TAIL ? s1[r] + nm : fmaf(s1[r], c, nm));
+  }
+  if (RAGGED) {
+    const int h = lc.h;
 #pragma unroll
     for (int r = 0; r < 32; ++r) {
-      x[r] = __builtin_amdgcn_exp2f(x[r] - m_safe);
-      psum += x[r];
+      const int key = 32 * (r >> 4) + ((r & 15) / 4) * 8 + 4 * h + (r % 4);
+      if (key >= nvalid) x[r] = 0.f;
     }
-  } else {
-    const float nm = -m_safe;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      x[r] = __builtin_amdgcn_exp2f(fmaf(s0[r], c, nm));
-      x[16 + r] = __builtin_amdgcn_exp2f(fmaf(s1[r], c, nm));
-    }
-    if (RAGGED) {
-#pragma unroll
-      for (int r = 0; r < 32; ++r) {
-        const int key = 32 * (r >> 4) + ((r & 15) / 4) * 8 + 4 * h + (r % 4);
-        if (key >= nvalid) x[r] = 0.f;
-      }
-    }
-#pragma unroll
-    for (int r = 0; r < 32; ++r) psum += x[r];
   }
+  float psum = 0.f;
+#pragma unroll
+  for (int r = 0; r < 32; ++r) psum += x[r];
   st.l += psum;
   if (TAIL) st.l_tail += psum;
-  // ---- O^T += V^T P^T: four contraction steps of 16 keys ----
-  // Transposed LDS read: lane j of a 16-lane group points at 4 channels of key (j >> 2) and
-  // receives channel (group base + j) of the group's four keys.
 #pragma unroll
   for (int step = 0; step < 4; ++step) {            // keys 16 step .. 16 step + 15
     u32x4 pw;
 #pragma unroll
     for (int i = 0; i < 4; ++i) pw[i] = pack_bf16(x[8 * step + 2 * i], x[8 * step + 2 * i + 1]);
-    const bf16x8 pb = __builtin_bit_cast(bf16x8, pw);
+    pb[step] = __builtin_bit_cast(bf16x8, pw);
+  }
+}
+
+// O^T += V^T P^T: four contraction steps of 16 keys.  Transposed LDS read: lane j of a
+// 16-lane group points at 4 channels of key (j >> 2) and receives channel (group base + j)
+// of the group's four keys.
+template <int VOFF>
+__device__ inline void pv_tile(State& st, const bf16x8 (&pb)[4], const LaneCtx& lc) {
+#pragma unroll
+  for (int step = 0; step < 4; ++step) {
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt) {
       LDS_PTR(unsigned char) vp =
@@ -324,15 +338,31 @@ __device__ inline void absorb_tile(State& st, const bf16x8 (&qreg)[8], const Lan
       const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<LDS_PTR(s16x4)>(vp + 8 * ROWB));
       const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
       const u32x4 aw = {l2.x, l2.y, h2.x, h2.y};
-      st.ot[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, aw), pb,
+      st.ot[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, aw), pb[step],
                                                           st.ot[dt], 0, 0, 0);
     }
   }
 }
 
+// One staged tile, start to finish (ragged tile, centroid tiles).
+template <bool TAIL, bool RAGGED, int KOFF, int KOFF2, int VOFF>
+__device__ inline void absorb_tile(State& st, const bf16x8 (&qreg)[8], const LaneCtx& lc,
+                                   LDS_PTR(const float) bias, int nvalid, float c) {
+  f32x16 s0, s1;
+  bf16x8 pb[4];
+  qk_tile<TAIL, KOFF, KOFF2>(s0, s1, qreg, lc);
+  const float m_safe = softmax_max<TAIL>(st, s0, s1, lc, bias, c);
+  softmax_exp<TAIL, RAGGED>(st, s0, s1, m_safe, pb, lc, nvalid, c);
+  pv_tile<VOFF>(st, pb, lc);
+}
+
+// LDS map of the staging area (byte offsets): K stages | V stages; Phase 2 reuses it as
+// khi | klo | vbar.
+constexpr int KST0 = 0, KST1 = TILEB, VST0 = 2 * TILEB, VST1 = 3 * TILEB;
+
 template <bool DENSE>
 __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
-  __shared__ __attribute__((aligned(1024))) unsigned char stage[2][2 * TILEB];   // [buf][K | V]
+  __shared__ __attribute__((aligned(1024))) unsigned char stage[4 * TILEB];   // K0 | K1 | V0 | V1
   __shared__ unsigned int chosen[2][MASK_WORDS];
   __shared__ __attribute__((aligned(16))) float bias_s[2][kTile];
 
@@ -354,7 +384,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
   const int tpb = p.B / kTile;                       // tiles per block: 1 or 2
   const int qb = tpb == 1 ? (wave >> 1) : 0;         // which of the workgroup's query blocks
   const float c = p.scale * 1.44269504088896340736f;
-  LDS_PTR(unsigned char) lds = (LDS_PTR(unsigned char)) & stage[0][0];
+  LDS_PTR(unsigned char) lds = (LDS_PTR(unsigned char)) & stage[0];
   const unsigned lds_addr = (unsigned)(unsigned long long)lds;
 
   LaneCtx lc;
@@ -454,32 +484,67 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
     }
     return true;
   };
-  auto issue_kv = [&](int tile, int buf) {
-    const int rows_avail = L - tile * kTile;
-    load_tile_async<true>(lc, kg + (size_t)tile * TILEB, rows_avail, lds_addr + buf * 2 * TILEB);
-    load_tile_async<false>(lc, vg + (size_t)tile * TILEB, rows_avail, lds_addr + buf * 2 * TILEB + TILEB);
+  auto issue_k = [&](int tile, int koff) {
+    load_tile_async<true>(lc, kg + (size_t)tile * TILEB, L - tile * kTile, lds_addr + koff);
+  };
+  auto issue_v = [&](int tile, int voff) {
+    load_tile_async<false>(lc, vg + (size_t)tile * TILEB, L - tile * kTile, lds_addr + voff);
   };
 
-  int tile_cur = 0, in_cur = 0, tile_nxt = 0, in_nxt = 0;
-  bool have = next_tile(tile_cur, in_cur);
-  if (have) issue_kv(tile_cur, 0);
-  // Two tiles per trip so that the stage index is a compile-time constant.
-  auto half_trip = [&](auto buf_tag) {
-    constexpr int BUF = decltype(buf_tag)::value;
-    const bool have_nxt = next_tile(tile_nxt, in_nxt);
+  // Software pipeline over tiles t = 0, 1, ...: K runs one tile ahead of V.  In trip t the
+  // wave issues S^T(t+1) on the matrix cores while the vector ALUs work through the softmax
+  // of tile t (the two are independent), then O^T += V(t)^T P(t)^T.  One barrier per trip:
+  // after it K(t+1) and V(t) have landed and K stage t&1 / V stage (t+1)&1 are free, so the
+  // loads of K(t+2) and V(t+1) go out right away.
+  int t0 = 0, in0 = 0, t1 = 0, in1 = 0, t2 = 0, in2 = 0;
+  bool have0 = next_tile(t0, in0);
+  bool have1 = false, have2 = false;
+  f32x16 sc0, sc1;                       // S^T of the current tile
+  if (have0) {
+    issue_k(t0, KST0);
+    have1 = next_tile(t1, in1);
     wait_async_loads();
-    __syncthreads();   // tile `cur` is complete in stage[BUF]; stage[BUF^1] is no longer read
-    if (have_nxt) issue_kv(tile_nxt, BUF ^ 1);
-    if ((in_cur >> qb) & 1)
-      absorb_tile<false, false, BUF * 2 * TILEB, 0, BUF * 2 * TILEB + TILEB>(st, qreg, lc, nullptr, kTile, c);
-    tile_cur = tile_nxt;
-    in_cur = in_nxt;
-    have = have_nxt;
+    __syncthreads();
+    if (have1) issue_k(t1, KST1);
+    issue_v(t0, VST0);
+    if ((in0 >> qb) & 1) qk_tile<false, KST0, 0>(sc0, sc1, qreg, lc);
+  }
+  auto trip = [&](auto parity_tag) {
+    constexpr int P = decltype(parity_tag)::value;       // parity of the current tile
+    constexpr int K_NEXT = P ? KST0 : KST1, K_FREE = P ? KST1 : KST0;
+    constexpr int V_CUR = P ? VST1 : VST0, V_FREE = P ? VST0 : VST1;
+    have2 = have1 && next_tile(t2, in2);
+    wait_async_loads();
+    __syncthreads();
+    if (have2) issue_k(t2, K_FREE);
+    if (have1) issue_v(t1, V_FREE);
+    const bool do_cur = (in0 >> qb) & 1;
+    const bool do_next = have1 && ((in1 >> qb) & 1);
+    if (do_cur && do_next) {
+      f32x16 sn0, sn1;
+      bf16x8 pb[4];
+      const float m_safe = softmax_max<false>(st, sc0, sc1, lc, nullptr, c);
+      // straight-line from here: S^T(t+1) on the matrix cores, exp / sum / pack on the VALU
+      qk_tile<false, K_NEXT, 0>(sn0, sn1, qreg, lc);
+      softmax_exp<false, false>(st, sc0, sc1, m_safe, pb, lc, kTile, c);
+      pv_tile<V_CUR>(st, pb, lc);
+      sc0 = sn0;
+      sc1 = sn1;
+    } else if (do_cur) {
+      bf16x8 pb[4];
+      const float m_safe = softmax_max<false>(st, sc0, sc1, lc, nullptr, c);
+      softmax_exp<false, false>(st, sc0, sc1, m_safe, pb, lc, kTile, c);
+      pv_tile<V_CUR>(st, pb, lc);
+    } else if (do_next) {
+      qk_tile<false, K_NEXT, 0>(sc0, sc1, qreg, lc);
+    }
+    t0 = t1; in0 = in1; have0 = have1;
+    t1 = t2; in1 = in2; have1 = have2;
   };
-  while (have) {
-    half_trip(std::integral_constant<int, 0>{});
-    if (!have) break;
-    half_trip(std::integral_constant<int, 1>{});
+  while (have0) {
+    trip(std::integral_constant<int, 0>{});
+    if (!have0) break;
+    trip(std::integral_constant<int, 1>{});
   }
 
   // ---- ragged last tile (L not a multiple of 64), if this workgroup attends it ----
@@ -490,11 +555,12 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
                                   (tpb == 1 ? (((chosen[1][jb >> 5] >> (jb & 31)) & 1u) << 1) : 0u));
     if (inm) {            // uniform over the workgroup
       __syncthreads();
-      issue_kv(tile, 0);
+      issue_k(tile, KST0);
+      issue_v(tile, VST0);
       wait_async_loads();
       __syncthreads();
       if ((inm >> qb) & 1)
-        absorb_tile<false, true, 0, 0, TILEB>(st, qreg, lc, nullptr, L - tile * kTile, c);
+        absorb_tile<false, true, KST0, 0, VST0>(st, qreg, lc, nullptr, L - tile * kTile, c);
     }
   }
 
