@@ -179,10 +179,18 @@ def main():
     fl_dense = dense_flops(L, d, h * b)
     attn_ms = stage[2]
     achieved = fl_attn / (attn_ms * 1e-3) / 1e12
+    # HBM-side traffic of the attention kernel per launch comes from separate rocprofv3 --pmc
+    # runs (counters cannot be read from inside this process); the committed summary applies
+    # to the default workload only.
     traffic = None
-    if args.traffic_json and os.path.exists(args.traffic_json):
-        with open(args.traffic_json) as f:
-            traffic = json.load(f)
+    tj = args.traffic_json
+    if tj is None and args.workload == "wan" and args.sparsity is None and args.block is None:
+        tj = os.path.join(ROOT, "profiles", "wan_r085_traffic.json")
+    if tj and os.path.exists(tj):
+        with open(tj) as f:
+            t = json.load(f)
+        traffic = {"fetch_bytes": t["fetch_bytes"], "write_bytes": t["write_bytes"],
+                   "algorithmic_bytes": t.get("algorithmic_bytes"), "source": t.get("source")}
     in_bytes = 3 * q.numel() * q.element_size()
     result = {
         "metric": "PISA attn ms/call & MFMA util at Wan2.1 shape, r=0.85; speedup vs dense",

@@ -366,11 +366,18 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
   __shared__ unsigned int chosen[2][MASK_WORDS];
   __shared__ __attribute__((aligned(16))) float bias_s[2][kTile];
 
-  // XCD-aware order: consecutive workgroup ids land on different XCDs, so each of the 8
-  // XCDs gets a contiguous range of (head, query super-tile) items and its L2 sees one head.
+  // Workgroup ids are dealt round-robin to the 8 XCDs.  Dense attention gives each XCD a
+  // contiguous range of (head, query tile) items, so one XCD's L2 serves one head whose tiles
+  // all its workgroups walk in the same order.  PISA workgroups walk different tile lists and
+  // mostly miss L2, so there all XCDs work on the same head at the same time instead: the
+  // misses of all 8 XCDs then fall on one or two heads' K/V (39 MB each), which the 256 MB
+  // Infinity Cache holds, rather than on eight heads at once.
   const int wg = blockIdx.x;
-  const int per_xcd = (p.total + 7) / 8;
-  const int item = (wg % 8) * per_xcd + wg / 8;
+  int item = ((wg >> 6) << 6) + ((wg & 7) << 3) + ((wg >> 3) & 7);   // 8 neighbours per XCD
+  if (DENSE) {
+    const int per_xcd = (p.total + 7) / 8;
+    item = (wg % 8) * per_xcd + wg / 8;
+  }
   if (item >= p.total) return;
   const size_t bh = item / p.n_super;
   const int sg = item % p.n_super;
@@ -654,7 +661,7 @@ hipError_t launch_attention_bf16(const Dims& dm, const AttnArgs& a, hipStream_t 
   p.total = p.n_super * dm.bh();
   p.scale = dm.scale;
   p.first_order = a.hsum != nullptr;
-  const int grid = ((p.total + 7) / 8) * 8;
+  const int grid = ((p.total + 63) / 64) * 64;
   if (a.dense) {
     hipLaunchKernelGGL(attn_bf16_kernel<true>, dim3(grid), dim3(256), 0, stream, p);
     return hipGetLastError();
