@@ -185,7 +185,7 @@ def main():
     traffic = None
     tj = args.traffic_json
     if tj is None and args.workload == "wan" and args.sparsity is None and args.block is None:
-        tj = os.path.join(ROOT, "profiles", "wan_r085_traffic.json")
+        tj = os.path.join(ROOT, "profiles", "wan_r085_traffic.txt")
     if tj and os.path.exists(tj):
         with open(tj) as f:
             t = json.load(f)
