@@ -112,14 +112,17 @@ int32_t pisa_select(const pisa_shape* shape, const double* qbar64, const double*
  *   out_t = N_t / D_t                         (hybrid equations; Alg. 1 lines 22-23)
  * with S_i = idx[i, :], U_i its complement, all inside one running-max softmax.
  *   kbar, vsum, hsum: as written by pisa_block_stats.  hsum == NULL drops the first-order
- *            term (the zeroth-order variant of the ablation study).
+ *            term (the zeroth-order variant of the ablation study).  kbar == vsum == NULL
+ *            drops the approximation altogether: plain block-sparse "keep-or-drop" attention
+ *            over S_i (Preliminaries, second equation; the ablation's baseline curve);
+ *            k_top must then be >= 1.
  *   idx      int32 [batch,heads,N,k_top]; must be in range, ascending and unique within a
  *            row (as pisa_select writes it) -- contents are not checked on the device.
  *   out      [batch,heads,seq_len,d] in shape->dtype
  *   lse      fp32 [batch,heads,seq_len]: log D_t; may be NULL.
  * k_top == N reproduces dense_attention; k_top == 0 is the pure approximation.
- * N up to 4096 blocks.  `workspace` must hold pisa_workspace_bytes(shape) when k_top < N
- * (it may be NULL when k_top == N); its contents are overwritten.
+ * N up to 4096 blocks.  `workspace` must hold pisa_workspace_bytes(shape) when k_top < N and
+ * kbar is given (it may be NULL otherwise); its contents are overwritten.
  */
 int32_t pisa_attention(const pisa_shape* shape, const void* q, const void* k, const void* v,
                        const float* kbar, const float* vsum, const float* hsum,

@@ -219,10 +219,11 @@ def dense_attention(q, k, v, block: int = 64, scale: Optional[float] = None,
 
 
 def pisa_forward(q, k, v, block: int = 64, sparsity: float = 0.85, first_order: bool = True,
-                 want_lse: bool = False):
+                 want_lse: bool = False, approximate: bool = True):
     """The whole hot path: block_stats -> select -> attention.
 
-    Returns dict(out, lse, idx, kth_gap, stats, k_top).
+    first_order=False gives the zeroth-order variant, approximate=False plain block-sparse
+    attention over the selected blocks.  Returns dict(out, lse, idx, kth_gap, stats, k_top).
     """
     shape = make_shape(q, block)
     n = num_blocks(q.shape[2], block)
@@ -230,7 +231,8 @@ def pisa_forward(q, k, v, block: int = 64, sparsity: float = 0.85, first_order: 
     ws = alloc_workspace(shape, q.device)
     stats = block_stats(q, k, v, block, ws)
     idx, gap = select(shape, stats["qbar64"], stats["kbar64"], k_top, ws)
-    out, lse = attention(shape, q, k, v, stats["kbar"], stats["vsum"],
-                         stats["hsum"] if first_order else None, idx, k_top, want_lse=want_lse,
-                         workspace=ws)
+    out, lse = attention(shape, q, k, v, stats["kbar"] if approximate else None,
+                         stats["vsum"] if approximate else None,
+                         stats["hsum"] if (first_order and approximate) else None, idx, k_top,
+                         want_lse=want_lse, workspace=ws)
     return dict(out=out, lse=lse, idx=idx, kth_gap=gap, stats=stats, k_top=k_top)

@@ -157,11 +157,13 @@ int32_t pisa_attention(const pisa_shape* shape, const void* q, const void* k, co
   if (k_top < 0 || k_top > dm.N)
     return fail(PISA_INVALID_ARG, "k_top = %d outside [0, N = %d]", k_top, dm.N);
   if (k_top > 0 && !idx) return fail(PISA_INVALID_ARG, "idx is NULL but k_top > 0");
-  if (k_top < dm.N && (!kbar || !vsum))
-    return fail(PISA_INVALID_ARG, "kbar and vsum must not be NULL when k_top < N");
+  if ((kbar == nullptr) != (vsum == nullptr))
+    return fail(PISA_INVALID_ARG, "kbar and vsum must both be given or both be NULL");
+  if (!kbar && k_top == 0)
+    return fail(PISA_INVALID_ARG, "keep-or-drop mode (kbar == vsum == NULL) needs k_top >= 1");
   if (dm.N > kMaxBlocks)
     return fail(PISA_UNSUPPORTED, "at most %d blocks are supported (N = %d)", kMaxBlocks, dm.N);
-  if (k_top < dm.N) {
+  if (k_top < dm.N && kbar) {
     size_t need = attention_workspace_bytes(dm);
     if (need > 0 && !workspace) return fail(PISA_INVALID_ARG, "workspace is NULL (need %zu bytes)", need);
     if (workspace_bytes < need)

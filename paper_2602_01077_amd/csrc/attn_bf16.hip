@@ -572,7 +572,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
   }
 
   // ---- Phase 2: centroid tiles (hi, lo, values) ----
-  const bool approx = !DENSE && p.k_top < N;
+  const bool approx = !DENSE && p.k_top < N && p.khi != nullptr;   // khi == nullptr: keep-or-drop
   if (approx) {
     const unsigned char* khg = reinterpret_cast<const unsigned char*>(p.khi + bh * (size_t)p.npad * D);
     const unsigned char* klg = reinterpret_cast<const unsigned char*>(p.klo + bh * (size_t)p.npad * D);
@@ -666,7 +666,7 @@ hipError_t launch_attention_bf16(const Dims& dm, const AttnArgs& a, hipStream_t 
     hipLaunchKernelGGL(attn_bf16_kernel<true>, dim3(grid), dim3(256), 0, stream, p);
     return hipGetLastError();
   }
-  if (a.k_top < dm.N) {
+  if (a.k_top < dm.N && a.kbar) {
     // carve the workspace: khi | klo | vbar | hpack | bias
     unsigned char* ws = static_cast<unsigned char*>(a.workspace);
     const size_t tile_elems = (size_t)dm.bh() * p.npad * D;

@@ -151,7 +151,7 @@ __global__ __launch_bounds__(256) void attn_fp32_kernel(P32 p) {
   }
 
   // ---- Phase 2: centroid tiles ----
-  if (!p.dense && p.k_top < N) {
+  if (!p.dense && p.k_top < N && p.kbar) {
     const float* kb = p.kbar + bh * (size_t)N * D;
     const float* vsm = p.vsum + bh * (size_t)N * D;
     const int last_rows = L - (N - 1) * p.B;
@@ -187,7 +187,7 @@ __global__ __launch_bounds__(256) void attn_fp32_kernel(P32 p) {
   l += __shfl_xor(l, 2);
   l_tail += __shfl_xor(l_tail, 1);
   l_tail += __shfl_xor(l_tail, 2);
-  if (!p.dense && p.hsum && p.k_top < N) {
+  if (!p.dense && p.hsum && p.kbar && p.k_top < N) {
     const float* hs = p.hsum + bh * (size_t)D * D;
     const float w = l_tail / (float)L * p.scale;
     for (int a = 0; a < D; ++a) {

@@ -89,7 +89,9 @@ def test_null_and_range_arguments():
     assert lib.pisa_attention(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, 4, FAKE, None, FAKE, 1 << 40, None) \
         == pisa.PISA_INVALID_ARG
     assert lib.pisa_attention(ctypes.byref(s), FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, 4, FAKE, None, FAKE, 1 << 40, None) \
-        == pisa.PISA_INVALID_ARG
+        == pisa.PISA_INVALID_ARG          # kbar without vsum
+    assert lib.pisa_attention(ctypes.byref(s), FAKE, FAKE, FAKE, None, None, None, None, 0, FAKE, None, FAKE, 1 << 40, None) \
+        == pisa.PISA_INVALID_ARG          # keep-or-drop with no block kept
     assert lib.pisa_select(ctypes.byref(s), FAKE, FAKE, -1, FAKE, None, FAKE, 1 << 40, None) == pisa.PISA_INVALID_ARG
     assert lib.pisa_select(ctypes.byref(s), FAKE, FAKE, 4, FAKE, None, FAKE, 8, None) == pisa.PISA_WORKSPACE_TOO_SMALL
     assert lib.pisa_select(ctypes.byref(s), FAKE, FAKE, 4, FAKE, None, None, 0, None) == pisa.PISA_INVALID_ARG

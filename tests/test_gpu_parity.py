@@ -52,19 +52,20 @@ def check_select(idx_gpu, gap_gpu, idx_ref, gap_ref, N, where=""):
     return soft
 
 
-def run_full_case(pisa, w, blocks_per_head=None, heads=None, first_order=True, seed_rows=0):
+def run_full_case(pisa, w, blocks_per_head=None, heads=None, first_order=True, approximate=True):
     """Runs stats -> select -> attention and dense on the GPU and checks each stage of
     the listed heads against the oracle (all query blocks unless blocks_per_head)."""
     q, k, v = make_qkv(w, device="cpu")
     qd, kd, vd = q.to(DEV), k.to(DEV), v.to(DEV)
-    res = pisa.pisa_forward(qd, kd, vd, w.block, w.sparsity, first_order=first_order, want_lse=True)
+    res = pisa.pisa_forward(qd, kd, vd, w.block, w.sparsity, first_order=first_order, want_lse=True,
+                            approximate=approximate)
     dense, dense_lse = pisa.dense_attention(qd, kd, vd, w.block, want_lse=True)
     torch.cuda.synchronize()
     scale = pisa.resolved_scale(w.head_dim)
     N, k_top = w.num_blocks, res["k_top"]
     assert k_top == w.topk
     tol = TOL[q.dtype]
-    mode = "hybrid" if first_order else "pisa0"
+    mode = ("hybrid" if first_order else "pisa0") if approximate else "sparse"
     worst = dict(pisa=0.0, dense=0.0, cos=1.0)
     for h in (range(w.heads) if heads is None else heads):
         Q, K, V, st, idx_ref, gap_ref = oracle_head(q, k, v, h, w.block, scale, k_top)
@@ -124,6 +125,8 @@ def test_fp32_cases(lib, L, H, d, B, r):
     (37, 1, 64, 0.0),            # shorter than a block
     (640, 2, 64, 1.0),           # k = 0
     (4200, 2, 64, 0.95),         # several Phase-2 tiles and a ragged centroid tile
+    (453, 2, 64, 0.5),           # odd number of blocks: the last workgroup holds one block
+    (128 * 9 + 3, 1, 128, 0.75), # block 128 with a 3-row last block
 ])
 def test_bf16_cases(lib, L, H, B, r):
     w = WORKLOADS["flux"].with_(name=f"bf16-{L}", heads=H, seq_len=L, block=B, sparsity=r, seed=20 + L,
@@ -136,6 +139,35 @@ def test_bf16_zeroth_order_only(lib):
     w = WORKLOADS["flux"].with_(name="bf16-0th", heads=2, seq_len=1500, sparsity=0.8, grid=None,
                                 block_offset_std=0.5)
     run_full_case(lib, w, first_order=False)
+
+
+@pytest.mark.parametrize("dtype,d,B", [("bf16", 128, 64), ("bf16", 128, 128), ("fp32", 64, 64)])
+def test_keep_or_drop_variant(lib, dtype, d, B):
+    """kbar = vsum = NULL: block-sparse attention over S_i only (masked-softmax equation)."""
+    w = WORKLOADS["tiny"].with_(name="sparse", heads=2, seq_len=1480, head_dim=d, dtype=dtype, block=B,
+                                sparsity=0.7, seed=31)
+    run_full_case(lib, w, approximate=False)
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("fp32", 64)])
+def test_batch_of_two(lib, dtype, d):
+    """batch > 1: (batch, head) pairs are independent problems laid out back to back."""
+    w = WORKLOADS["tiny"].with_(name="batch2", heads=2, seq_len=453, head_dim=d, dtype=dtype, sparsity=0.6, seed=41)
+    scale = lib.resolved_scale(d)
+    parts = [make_qkv(w, batch_index=b) for b in range(2)]
+    q, k, v = (torch.cat([p[i] for p in parts], dim=0) for i in range(3))
+    res = lib.pisa_forward(q.to(DEV), k.to(DEV), v.to(DEV), w.block, w.sparsity, want_lse=True)
+    torch.cuda.synchronize()
+    for b in range(2):
+        for h in range(w.heads):
+            Q, K, V = head_np(q, b, h), head_np(k, b, h), head_np(v, b, h)
+            st = po.block_stats(Q, K, V, w.block)
+            idx_ref, gap_ref = po.select(st["qbar"], st["kbar"], scale, res["k_top"])
+            idx_gpu = res["idx"][b, h].cpu().numpy()
+            check_select(idx_gpu, None, idx_ref, gap_ref, w.num_blocks, where=f" batch {b} head {h}")
+            ref, _ = po.attention_head(Q, K, V, w.block, idx_gpu, scale, "hybrid", stats=st)
+            rel, cos = row_errors(res["out"][b, h].float().cpu().numpy(), ref)
+            assert rel <= TOL[q.dtype] and cos >= COS_MIN, (b, h, rel, cos)
 
 
 @pytest.mark.parametrize("dtype,d,B", [("bf16", 128, 64), ("bf16", 128, 128), ("fp32", 64, 64), ("fp32", 128, 128)])
