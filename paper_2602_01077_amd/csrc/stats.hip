@@ -6,8 +6,6 @@
 // blocks of one head, keeps its share of H in registers, and writes one partial
 // d x d matrix; a second kernel adds the partials in chunk order, so hsum is
 // bit-identical from run to run.
-#include <hip/hip_bf16.h>
-
 #include "common.h"
 
 namespace pisa {
@@ -15,9 +13,8 @@ namespace {
 
 template <typename T> __device__ inline float to_f32(T x);
 template <> __device__ inline float to_f32<float>(float x) { return x; }
-template <> __device__ inline float to_f32<__hip_bfloat16>(__hip_bfloat16 x) { return __bfloat162float(x); }
 
-// Generic (VALU) statistics kernel, any supported dtype.
+// Vector-ALU statistics kernel (the fp32 build; bf16 inputs take the matrix-core kernel).
 //   LDS: kc[64][D] centred keys, vs[64][D] values, column-sum scratch.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void stats_kernel(
@@ -51,7 +48,7 @@ __global__ __launch_bounds__(256) void stats_kernel(
   for (int j = j_begin; j < j_end; ++j) {
     const int row0 = j * B;
     const int rows = min(B, L - row0);
-    // ---- column sums in fp64 (exact for bf16 inputs) ----
+    // ---- column sums in fp64 ----
     {
       const int col = tid % D, part = tid / D;
       double sq = 0.0, sk = 0.0, sv = 0.0;
@@ -136,7 +133,7 @@ __global__ __launch_bounds__(256) void reduce_h_kernel(const float* __restrict__
 
 }  // namespace
 
-hipError_t launch_block_stats_bf16_b64(const Dims& dm, const void* q, const void* k, const void* v,
+hipError_t launch_block_stats_bf16(const Dims& dm, const void* q, const void* k, const void* v,
                                        float* qbar, float* kbar, float* vsum,
                                        double* qbar64, double* kbar64, float* partial_h,
                                        const StatsPlan& plan, hipStream_t stream);
@@ -151,12 +148,10 @@ hipError_t launch_block_stats(const Dims& dm, const void* q, const void* k, cons
   hipLaunchKernelGGL((stats_kernel<T, DD>), grid, dim3(256), 0, stream, (const T*)q, (const T*)k, \
                      (const T*)v, qbar, kbar, vsum, qbar64, kbar64, partial_h, dm.L, dm.B, dm.N,   \
                      plan.chunk_blocks, plan.n_chunks)
-  if (dm.dtype == PISA_BF16 && dm.B == kTile) {
-    hipError_t e = launch_block_stats_bf16_b64(dm, q, k, v, qbar, kbar, vsum, qbar64, kbar64,
-                                               partial_h, plan, stream);
+  if (dm.dtype == PISA_BF16) {
+    hipError_t e = launch_block_stats_bf16(dm, q, k, v, qbar, kbar, vsum, qbar64, kbar64,
+                                           partial_h, plan, stream);
     if (e != hipSuccess) return e;
-  } else if (dm.dtype == PISA_BF16) {
-    PISA_STATS(__hip_bfloat16, 128);
   } else if (dm.d == 64) {
     PISA_STATS(float, 64);
   } else {

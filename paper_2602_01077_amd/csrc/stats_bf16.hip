@@ -1,7 +1,7 @@
-// pisa_block_stats for bf16 inputs, head_dim 128, block 64: one streaming pass (Alg. 1 line 1).
+// pisa_block_stats for bf16 inputs, head_dim 128, block 64 or 128: one streaming pass (Alg. 1 line 1).
 //
 // Grid (n_chunks, batch*heads); a workgroup of 4 waves walks `chunk_blocks` consecutive
-// 64-token blocks of one head.  Per block:
+// blocks of one head.  Per 64-token (sub-)block:
 //   * wave w loads rows 16w..16w+15 of the Q, K and V tiles, one 4-byte channel pair per
 //     lane (a wave-load is one 256-byte row), and adds them in fp64 (exact for bf16 data);
 //     the four waves' partial column sums meet in LDS and are added in wave order;
@@ -61,15 +61,26 @@ __device__ inline bf16x8 read_operand(LDS_PTR(const unsigned char) tile, int lan
   return __builtin_bit_cast(bf16x8, w);
 }
 
+// TPB = tiles (64-token sub-blocks) per block: 1 for block 64, 2 for block 128.  With two
+// sub-blocks each is centred on its OWN mean c_s for the matrix-core contraction, and the
+// block's H_j follows from  sum_n (k_n - c_s)^T v_n = sum_n (k_n - kbar_j)^T v_n + (kbar_j - c_s)^T Vhat_s :
+//   H_j = sum_s [ A_s + (c_s - kbar_j)^T Vhat_s ],
+// a small rank-one correction per sub-block (c_s is close to kbar_j, so nothing cancels).
+template <int TPB>
 __global__ __launch_bounds__(256, 2) void stats_bf16_kernel(
     const unsigned int* __restrict__ q, const unsigned int* __restrict__ k, const unsigned int* __restrict__ v,
     float* __restrict__ qbar, float* __restrict__ kbar, float* __restrict__ vsum,
     double* __restrict__ qbar64, double* __restrict__ kbar64, float* __restrict__ partial_h,
     int L, int N, int chunk_blocks, int n_chunks) {
+  constexpr int B = TPB * kTile;
   __shared__ __attribute__((aligned(1024))) unsigned char khi_s[TILEB];
   __shared__ __attribute__((aligned(1024))) unsigned char klo_s[TILEB];
   __shared__ __attribute__((aligned(1024))) unsigned char v_s[TILEB];
   __shared__ __attribute__((aligned(16))) double red[3][4][D];
+  __shared__ double tot[3][D];          // block totals over the sub-blocks (q, k, v)
+  __shared__ double csub[2][D];         // sub-block key means c_s
+  __shared__ float vsub[2][D];          // sub-block value sums Vhat_s
+  __shared__ float dks[2][D];           // c_s - kbar_j
   __shared__ float kmean_s[D];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -82,6 +93,7 @@ __global__ __launch_bounds__(256, 2) void stats_bf16_kernel(
   LDS_PTR(unsigned char) khi = (LDS_PTR(unsigned char))khi_s;
   LDS_PTR(unsigned char) klo = (LDS_PTR(unsigned char))klo_s;
   LDS_PTR(unsigned char) vt = (LDS_PTR(unsigned char))v_s;
+  const int lam = lane & 31, h = lane >> 5;
 
   f32x16 acc[4];
 #pragma unroll
@@ -90,87 +102,125 @@ __global__ __launch_bounds__(256, 2) void stats_bf16_kernel(
   const int j_begin = chunk * chunk_blocks;
   const int j_end = min(N, j_begin + chunk_blocks);
   for (int j = j_begin; j < j_end; ++j) {
-    const int row0 = j * kTile;
-    const int rows = min(kTile, L - row0);
-    // ---- load this wave's 16 rows, one channel pair per lane ----
-    unsigned int kx[16], vx[16], qx[16];
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int n = 16 * wave + i;
-      kx[i] = vx[i] = qx[i] = 0u;
-      if (n < rows) {
-        const size_t o = (size_t)(row0 + n) * (D / 2) + lane;
-        qx[i] = qh[o];
-        kx[i] = kh[o];
-        vx[i] = vh[o];
-      }
-    }
-    // ---- fp64 column sums of the 16 rows (zeros of absent rows add nothing) ----
-    double sq0 = 0, sq1 = 0, sk0 = 0, sk1 = 0, sv0 = 0, sv1 = 0;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      sq0 += (double)__uint_as_float(qx[i] << 16);
-      sq1 += (double)__uint_as_float(qx[i] & 0xffff0000u);
-      sk0 += (double)__uint_as_float(kx[i] << 16);
-      sk1 += (double)__uint_as_float(kx[i] & 0xffff0000u);
-      sv0 += (double)__uint_as_float(vx[i] << 16);
-      sv1 += (double)__uint_as_float(vx[i] & 0xffff0000u);
-    }
-    *reinterpret_cast<f64x2*>(&red[0][wave][2 * lane]) = (f64x2){sq0, sq1};
-    *reinterpret_cast<f64x2*>(&red[1][wave][2 * lane]) = (f64x2){sk0, sk1};
-    *reinterpret_cast<f64x2*>(&red[2][wave][2 * lane]) = (f64x2){sv0, sv1};
-    __syncthreads();
-    if (tid < D) {
-      const double sq = ((red[0][0][tid] + red[0][1][tid]) + red[0][2][tid]) + red[0][3][tid];
-      const double sk = ((red[1][0][tid] + red[1][1][tid]) + red[1][2][tid]) + red[1][3][tid];
-      const double sv = ((red[2][0][tid] + red[2][1][tid]) + red[2][2][tid]) + red[2][3][tid];
-      const double qm = sq / (double)rows, km = sk / (double)rows;
-      const size_t o = (bh * N + j) * D + tid;
-      qbar[o] = (float)qm;
-      kbar[o] = (float)km;
-      vsum[o] = (float)sv;
-      qbar64[o] = qm;
-      kbar64[o] = km;
-      kmean_s[tid] = (float)km;
-    }
-    __syncthreads();
-    // ---- centre K, split hi/lo, stage with V ----
-    {
-      const float m0 = kmean_s[2 * lane], m1 = kmean_s[2 * lane + 1];
+    const int block_rows = min(B, L - j * B);
+    int n_sub = 0;
+    for (int sub = 0; sub < TPB; ++sub) {
+      const int row0 = j * B + sub * kTile;
+      const int rows = min(kTile, L - row0);
+      if (rows <= 0) break;                       // uniform: the block ends inside its first half
+      n_sub = sub + 1;
+      // ---- load this wave's 16 rows, one channel pair per lane ----
+      unsigned int kx[16], vx[16], qx[16];
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const int n = 16 * wave + i;
-        unsigned int hi = 0u, lo = 0u;
+        kx[i] = vx[i] = qx[i] = 0u;
         if (n < rows) {
-          const float c0 = __uint_as_float(kx[i] << 16) - m0;
-          const float c1 = __uint_as_float(kx[i] & 0xffff0000u) - m1;
-          hi = pack_bf16(c0, c1);
-          lo = pack_bf16(c0 - __uint_as_float(hi << 16), c1 - __uint_as_float(hi & 0xffff0000u));
+          const size_t o = (size_t)(row0 + n) * (D / 2) + lane;
+          qx[i] = qh[o];
+          kx[i] = kh[o];
+          vx[i] = vh[o];
         }
-        const int a = swz_pair(n, lane);
-        *reinterpret_cast<LDS_PTR(unsigned int)>(khi + a) = hi;
-        *reinterpret_cast<LDS_PTR(unsigned int)>(klo + a) = lo;
-        *reinterpret_cast<LDS_PTR(unsigned int)>(vt + a) = vx[i];
       }
-    }
-    __syncthreads();
-    // ---- H[32 wave .. +32][all 128] += Kc^T V over the 64 tokens ----
+      // ---- fp64 column sums of the 16 rows (zeros of absent rows add nothing) ----
+      double sq0 = 0, sq1 = 0, sk0 = 0, sk1 = 0, sv0 = 0, sv1 = 0;
 #pragma unroll
-    for (int step = 0; step < 4; ++step) {
-      const bf16x8 ahi = read_operand(khi, lane, step, wave);
-      const bf16x8 alo = read_operand(klo, lane, step, wave);
-#pragma unroll
-      for (int bt = 0; bt < 4; ++bt) {
-        const bf16x8 b = read_operand(vt, lane, step, bt);
-        acc[bt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ahi, b, acc[bt], 0, 0, 0);
-        acc[bt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(alo, b, acc[bt], 0, 0, 0);
+      for (int i = 0; i < 16; ++i) {
+        sq0 += (double)__uint_as_float(qx[i] << 16);
+        sq1 += (double)__uint_as_float(qx[i] & 0xffff0000u);
+        sk0 += (double)__uint_as_float(kx[i] << 16);
+        sk1 += (double)__uint_as_float(kx[i] & 0xffff0000u);
+        sv0 += (double)__uint_as_float(vx[i] << 16);
+        sv1 += (double)__uint_as_float(vx[i] & 0xffff0000u);
       }
+      *reinterpret_cast<f64x2*>(&red[0][wave][2 * lane]) = (f64x2){sq0, sq1};
+      *reinterpret_cast<f64x2*>(&red[1][wave][2 * lane]) = (f64x2){sk0, sk1};
+      *reinterpret_cast<f64x2*>(&red[2][wave][2 * lane]) = (f64x2){sv0, sv1};
+      __syncthreads();
+      if (tid < D) {
+        const double sq = ((red[0][0][tid] + red[0][1][tid]) + red[0][2][tid]) + red[0][3][tid];
+        const double sk = ((red[1][0][tid] + red[1][1][tid]) + red[1][2][tid]) + red[1][3][tid];
+        const double sv = ((red[2][0][tid] + red[2][1][tid]) + red[2][2][tid]) + red[2][3][tid];
+        const double cm = sk / (double)rows;
+        if (TPB == 1) {
+          const double qm = sq / (double)rows;
+          const size_t o = (bh * N + j) * D + tid;
+          qbar[o] = (float)qm;
+          kbar[o] = (float)cm;
+          vsum[o] = (float)sv;
+          qbar64[o] = qm;
+          kbar64[o] = cm;
+        } else {
+          tot[0][tid] = sub == 0 ? sq : tot[0][tid] + sq;
+          tot[1][tid] = sub == 0 ? sk : tot[1][tid] + sk;
+          tot[2][tid] = sub == 0 ? sv : tot[2][tid] + sv;
+          csub[sub][tid] = cm;
+          vsub[sub][tid] = (float)sv;
+        }
+        kmean_s[tid] = (float)cm;
+      }
+      __syncthreads();
+      // ---- centre K on the sub-block mean, split hi/lo, stage with V ----
+      {
+        const float m0 = kmean_s[2 * lane], m1 = kmean_s[2 * lane + 1];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int n = 16 * wave + i;
+          unsigned int hi = 0u, lo = 0u;
+          if (n < rows) {
+            const float c0 = __uint_as_float(kx[i] << 16) - m0;
+            const float c1 = __uint_as_float(kx[i] & 0xffff0000u) - m1;
+            hi = pack_bf16(c0, c1);
+            lo = pack_bf16(c0 - __uint_as_float(hi << 16), c1 - __uint_as_float(hi & 0xffff0000u));
+          }
+          const int a = swz_pair(n, lane);
+          *reinterpret_cast<LDS_PTR(unsigned int)>(khi + a) = hi;
+          *reinterpret_cast<LDS_PTR(unsigned int)>(klo + a) = lo;
+          *reinterpret_cast<LDS_PTR(unsigned int)>(vt + a) = vx[i];
+        }
+      }
+      __syncthreads();
+      // ---- H[32 wave .. +32][all 128] += Kc^T V over the 64 tokens ----
+#pragma unroll
+      for (int step = 0; step < 4; ++step) {
+        const bf16x8 ahi = read_operand(khi, lane, step, wave);
+        const bf16x8 alo = read_operand(klo, lane, step, wave);
+#pragma unroll
+        for (int bt = 0; bt < 4; ++bt) {
+          const bf16x8 b = read_operand(vt, lane, step, bt);
+          acc[bt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ahi, b, acc[bt], 0, 0, 0);
+          acc[bt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(alo, b, acc[bt], 0, 0, 0);
+        }
+      }
+      // the next sub-block's LDS writes are separated from these reads by its two barriers
     }
-    // the next block's LDS writes are separated from these reads by its two barriers
+    if (TPB == 2) {
+      // ---- block outputs from the sub-block totals, then the rank-one corrections ----
+      if (tid < D) {
+        const double qm = tot[0][tid] / (double)block_rows, km = tot[1][tid] / (double)block_rows;
+        const size_t o = (bh * N + j) * D + tid;
+        qbar[o] = (float)qm;
+        kbar[o] = (float)km;
+        vsum[o] = (float)tot[2][tid];
+        qbar64[o] = qm;
+        kbar64[o] = km;
+        for (int sub = 0; sub < n_sub; ++sub) dks[sub][tid] = (float)(csub[sub][tid] - km);
+      }
+      __syncthreads();
+      for (int sub = 0; sub < n_sub; ++sub) {
+#pragma unroll
+        for (int bt = 0; bt < 4; ++bt) {
+          const float vb = vsub[sub][32 * bt + lam];
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            acc[bt][r] = fmaf(dks[sub][32 * wave + (r / 4) * 8 + 4 * h + (r % 4)], vb, acc[bt][r]);
+        }
+      }
+      __syncthreads();                            // dks / vsub / tot are rewritten by the next block
+    }
   }
   // acc[bt][r] = H[32 wave + (r/4)*8 + 4h + r%4][32 bt + lam]
   float* ph = partial_h + (bh * n_chunks + chunk) * (size_t)D * D;
-  const int lam = lane & 31, h = lane >> 5;
 #pragma unroll
   for (int bt = 0; bt < 4; ++bt)
 #pragma unroll
@@ -180,13 +230,19 @@ __global__ __launch_bounds__(256, 2) void stats_bf16_kernel(
 
 }  // namespace
 
-hipError_t launch_block_stats_bf16_b64(const Dims& dm, const void* q, const void* k, const void* v,
-                                       float* qbar, float* kbar, float* vsum,
-                                       double* qbar64, double* kbar64, float* partial_h,
-                                       const StatsPlan& plan, hipStream_t stream) {
-  hipLaunchKernelGGL(stats_bf16_kernel, dim3(plan.n_chunks, dm.bh()), dim3(256), 0, stream,
-                     (const unsigned int*)q, (const unsigned int*)k, (const unsigned int*)v, qbar, kbar,
-                     vsum, qbar64, kbar64, partial_h, dm.L, dm.N, plan.chunk_blocks, plan.n_chunks);
+hipError_t launch_block_stats_bf16(const Dims& dm, const void* q, const void* k, const void* v,
+                                   float* qbar, float* kbar, float* vsum,
+                                   double* qbar64, double* kbar64, float* partial_h,
+                                   const StatsPlan& plan, hipStream_t stream) {
+  const dim3 grid(plan.n_chunks, dm.bh());
+  if (dm.B == kTile)
+    hipLaunchKernelGGL(stats_bf16_kernel<1>, grid, dim3(256), 0, stream, (const unsigned int*)q,
+                       (const unsigned int*)k, (const unsigned int*)v, qbar, kbar, vsum, qbar64, kbar64,
+                       partial_h, dm.L, dm.N, plan.chunk_blocks, plan.n_chunks);
+  else
+    hipLaunchKernelGGL(stats_bf16_kernel<2>, grid, dim3(256), 0, stream, (const unsigned int*)q,
+                       (const unsigned int*)k, (const unsigned int*)v, qbar, kbar, vsum, qbar64, kbar64,
+                       partial_h, dm.L, dm.N, plan.chunk_blocks, plan.n_chunks);
   return hipGetLastError();
 }
 
