@@ -1,0 +1,100 @@
+"""Measurement sweeps on synthetic inputs (run on the GPU machine):
+
+    python -m paper_2602_01077_amd.study error  [--workload wan] [--heads 8]
+    python -m paper_2602_01077_amd.study speed  [--lengths 4096 8192 ...]
+
+`error`  normalised L1 error against the library's dense_attention,
+         sum|O - O_dense| / sum|O_dense|, for the keep-or-drop, zeroth-order and hybrid
+         variants over a range of densities (the quantity of the paper's ablation figure
+         "Relative error with respect to dense attention", here on synthetic inputs).
+`speed`  ms per call of dense_attention and of the whole PISA path over sequence lengths
+         and densities at the paper's kernel-study shape B2-H16-D128 ("Kernel Efficiency
+         Evaluation").
+Both print one JSON line per point.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+
+import torch
+
+import paper_2602_01077_amd as pisa
+from workloads import WORKLOADS, make_qkv
+
+
+def _time_ms(fn, iters):
+    fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+def error_study(args):
+    w = WORKLOADS[args.workload]
+    heads = list(range(0, w.heads, max(1, w.heads // args.heads)))[: args.heads]
+    q, k, v = make_qkv(w, device="cuda:0", heads=heads)
+    dense, _ = pisa.dense_attention(q, k, v, w.block)
+    den = dense.float().abs().sum().item()
+    for r in args.sparsity:
+        row = {"workload": w.name, "heads": len(heads), "seq_len": w.seq_len, "block": w.block,
+               "sparsity": r, "density": round(1 - r, 4)}
+        for name, kw in (("keep_or_drop", dict(approximate=False)),
+                         ("zeroth_order", dict(first_order=False)),
+                         ("hybrid", dict())):
+            if name == "keep_or_drop" and pisa.topk_count(w.num_blocks, r) == 0:
+                row[name] = None
+                continue
+            out = pisa.pisa_forward(q, k, v, w.block, r, **kw)["out"]
+            row[name] = (out.float() - dense.float()).abs().sum().item() / den
+        print(json.dumps(row), flush=True)
+
+
+def speed_study(args):
+    dev = torch.device("cuda:0")
+    base = WORKLOADS["wan"]
+    for L in args.lengths:
+        w = base.with_(name=f"B2-H16-D128-L{L}", heads=16, seq_len=L, grid=None, block_offset_std=0.5)
+        parts = [make_qkv(w, device=dev, batch_index=b) for b in range(2)]
+        q, k, v = (torch.cat([p[i] for p in parts], dim=0).contiguous() for i in range(3))
+        shape = pisa.make_shape(q, w.block)
+        ws = pisa.alloc_workspace(shape, dev)
+        out = torch.empty_like(q)
+        dense_ms = _time_ms(lambda: pisa.dense_attention(q, k, v, w.block, out=out), args.iters)
+        for r in args.sparsity:
+            k_top = pisa.topk_count(w.num_blocks, r)
+
+            def path():
+                st = pisa.block_stats(q, k, v, w.block, ws)
+                idx, _ = pisa.select(shape, st["qbar64"], st["kbar64"], k_top, ws, want_gap=False)
+                pisa.attention(shape, q, k, v, st["kbar"], st["vsum"], st["hsum"], idx, k_top, out=out,
+                               workspace=ws)
+
+            ms = _time_ms(path, args.iters)
+            print(json.dumps({"shape": "B2-H16-D128", "seq_len": L, "density": round(1 - r, 4),
+                              "k_top": k_top, "dense_ms": round(dense_ms, 4), "pisa_ms": round(ms, 4),
+                              "speedup": round(dense_ms / ms, 3)}), flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    sub = ap.add_subparsers(dest="cmd", required=True)
+    e = sub.add_parser("error")
+    e.add_argument("--workload", default="wan", choices=list(WORKLOADS))
+    e.add_argument("--heads", type=int, default=8)
+    e.add_argument("--sparsity", type=float, nargs="+", default=[0.5, 0.75, 0.8, 0.85, 0.875, 0.9, 0.95])
+    s = sub.add_parser("speed")
+    s.add_argument("--lengths", type=int, nargs="+", default=[4096, 8192, 16384, 32768, 65536])
+    s.add_argument("--sparsity", type=float, nargs="+", default=[0.3, 0.5, 0.7, 0.875])
+    s.add_argument("--iters", type=int, default=5)
+    args = ap.parse_args()
+    (error_study if args.cmd == "error" else speed_study)(args)
+
+
+if __name__ == "__main__":
+    main()
