@@ -18,8 +18,9 @@ What is computed (citations are to the paper):
   line 1) with the definitions of the block centroid and of `H_j` from the
   "Formulation" / "Global First-Order Correction" paragraphs.
 * `select`       -- block-wise top-k of pooled scores (Alg. 1 line 2; the score
-  is the covariance-aware score equation without its `log(M_j + eps)` term,
-  which the paper switches on for image models only).
+  is the covariance-aware score equation; its `log(M_j + eps)` term, which the
+  paper switches on for image models only, enters as an optional column bias
+  built from `block_heterogeneity`).
 * `attention_rows` -- the output definition: `o_t = N_t / D_t` with the exact
   term, the block-wise zeroth-order term and one of the first-order variants
   (block-wise first-order equations; hybrid equations with the global `H`).
@@ -120,14 +121,31 @@ def pooled_logits(qbar, kbar, scale: float) -> np.ndarray:
     return scale * (_f64(qbar) @ _f64(kbar).T)
 
 
-def select(qbar, kbar, scale: float, k: int):
+def block_heterogeneity(Hj, hsum, kind: str = "spectral") -> np.ndarray:
+    """M_j = || H_j - Hbar ||, Hbar = hsum / N  (Covariance-Aware Block Selection).
+    kind: "spectral" (operator 2-norm, the norm the error analysis uses) or "frobenius"."""
+    Hj = _f64(Hj)
+    N = Hj.shape[0]
+    Dm = Hj - _f64(hsum)[None] / N
+    if kind == "spectral":
+        return np.array([np.linalg.norm(Dm[j], 2) for j in range(N)])
+    if kind == "frobenius":
+        return np.sqrt((Dm * Dm).sum(axis=(1, 2)))
+    raise ValueError(kind)
+
+
+def select(qbar, kbar, scale: float, k: int, col_bias=None):
     """Top-k key blocks per query block.
 
     Returns (idx[N, k] int32 ascending, gap[N]) where gap is the logit
     difference between the k-th and (k+1)-th best block (inf when k is 0 or N).
     Softmax over a row is monotone, so ranking uses the logits directly.
+    col_bias[j] (optional) is added to every logit of key block j: with
+    col_bias = log(M_j + eps) this is the covariance-aware score.
     """
     z = pooled_logits(qbar, kbar, scale)
+    if col_bias is not None:
+        z = z + _f64(col_bias)[None, :]
     Nq, N = z.shape
     order = np.argsort(-z, axis=1, kind="stable")       # ties -> lower index first
     idx = np.sort(order[:, :k], axis=1).astype(np.int32)

@@ -389,3 +389,52 @@ def test_error_shrinks_with_key_spread_and_beats_sparse():
         if prev is not None:
             assert err["pisa0"] < prev["pisa0"] and err["pisa1"] < prev["pisa1"]
         prev = err
+
+
+# --- covariance-aware selection -----------------------------------------------------------
+def test_covariance_aware_score_is_alpha_times_M():
+    """Adding log(M_j + eps) to the pooled logit ranks blocks by exp(z_ij) (M_j + eps)
+    (Covariance-Aware Block Selection and its appendix derivation: routing factor
+    exp(q kbar_j) M_j / Mbar, the constant Mbar drops out of the softmax)."""
+    L, B, d = 160, 16, 5
+    N = L // B
+    rng = np.random.default_rng(21)
+    Q, K, V = rand_qkv(L, d, rng)
+    st = po.block_stats(Q, K, V, B, per_block_H=True)
+    eps = 1e-6
+    for kind in ("spectral", "frobenius"):
+        M = po.block_heterogeneity(st["Hj"], st["hsum"], kind)
+        assert M.shape == (N,) and np.all(M > 0)
+        idx, _ = po.select(st["qbar"], st["kbar"], 0.5, 3, col_bias=np.log(M + eps))
+        z = po.pooled_logits(st["qbar"], st["kbar"], 0.5)
+        for i in range(N):
+            w = np.exp(z[i]) * (M + eps)
+            assert sorted(np.argsort(-w, kind="stable")[:3].tolist()) == idx[i].tolist()
+    # spectral <= Frobenius <= sqrt(rank) * spectral
+    Ms = po.block_heterogeneity(st["Hj"], st["hsum"], "spectral")
+    Mf = po.block_heterogeneity(st["Hj"], st["hsum"], "frobenius")
+    assert np.all(Ms <= Mf * (1 + 1e-12)) and np.all(Mf <= math.sqrt(d) * Ms * (1 + 1e-12))
+
+
+def test_covariance_bias_is_neutral_when_blocks_are_alike():
+    """Equal M_j for all blocks shifts every logit alike, so the selection is unchanged;
+    a block whose H_j stands out is pulled into S_i."""
+    L, B, d = 256, 16, 4
+    N = L // B
+    rng = np.random.default_rng(22)
+    Q = rng.standard_normal((L, d))
+    cent = rng.standard_normal((N, d))
+    dev = 0.3 * rng.standard_normal((B, d))
+    w = rng.standard_normal((B, d))
+    K = np.repeat(cent, B, axis=0) + np.tile(dev, (N, 1))
+    V = np.tile(w, (N, 1))
+    V[5 * B:6 * B] *= 30.0                      # block 5: a much larger H_5
+    st = po.block_stats(Q, K, V, B, per_block_H=True)
+    M = po.block_heterogeneity(st["Hj"], st["hsum"], "spectral")
+    others = np.delete(M, 5)
+    assert np.allclose(others, others[0], rtol=1e-9) and M[5] > 5 * others[0]
+    plain, _ = po.select(st["qbar"], st["kbar"], 0.5, 2)
+    biased, _ = po.select(st["qbar"], st["kbar"], 0.5, 2, col_bias=np.log(M + 1e-6))
+    assert np.all((biased == 5).any(axis=1))     # every query block now keeps block 5 exact
+    flat, _ = po.select(st["qbar"], st["kbar"], 0.5, 2, col_bias=np.full(N, math.log(others[0])))
+    assert np.array_equal(flat, plain)
