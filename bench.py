@@ -81,6 +81,8 @@ def main():
     ap.add_argument("--block", type=int, default=None)
     ap.add_argument("--dense-steps", type=int, default=3, help="timed dense_attention calls (0 = skip)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--covariance-aware", choices=["spectral", "frobenius"], default=None,
+                    help="add the covariance-aware selection score (pisa_block_heterogeneity) to the step")
     ap.add_argument("--copy-calibration", type=int, default=0,
                     help="also run this many plain device copies of 1 GiB (reference for rocprofv3 --pmc byte counters)")
     ap.add_argument("--traffic-json", default=None,
@@ -121,13 +123,19 @@ def main():
     gap = torch.empty(b, h, N, dtype=f32, device=dev)
     out = torch.empty_like(q)
 
+    norm = {None: None, "spectral": pisa.PISA_NORM_SPECTRAL, "frobenius": pisa.PISA_NORM_FROBENIUS}[
+        args.covariance_aware]
+
     def step(events=None):
         if events:
             events[0].record()
         pisa.block_stats_into(shape, q, k, v, stats, ws)
         if events:
             events[1].record()
-        pisa.select_into(shape, stats["qbar64"], stats["kbar64"], k_top, idx, gap, ws)
+        log_m = None
+        if norm is not None:       # counted in the select stage
+            log_m = pisa.block_heterogeneity(shape, k, v, stats["kbar64"], norm, 1e-6, ws)
+        pisa.select_into(shape, stats["qbar64"], stats["kbar64"], k_top, idx, gap, ws, log_m)
         if events:
             events[2].record()
         pisa.attention(shape, q, k, v, stats["kbar"], stats["vsum"], stats["hsum"], idx, k_top, out=out,
@@ -198,7 +206,9 @@ def main():
         "warmup": args.warmup, "ms_per_step": round(wall_ms, 4), "higher_is_better": False,
         "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": f"{w.name}: B={b} H={h} N={L} d={d} {w.dtype} block={w.block} "
-                               f"sparsity={w.sparsity} (k={k_top} of {N} blocks exact)",
+                               f"sparsity={w.sparsity} (k={k_top} of {N} blocks exact)"
+                               + (f" covariance-aware selection ({args.covariance_aware} norm)"
+                                  if args.covariance_aware else ""),
                    "seed": w.seed},
         "stages_ms": {"pisa_block_stats": round(stage[0], 4), "pisa_select": round(stage[1], 4),
                       "pisa_attention": round(stage[2], 4)},

@@ -6,6 +6,7 @@
  *
  *   pisa_block_stats   Alg. 1 line 1   ("Prepare": block means, block value sums, global H)
  *   pisa_select        Alg. 1 line 2   (block-wise top-k of pooled scores)
+ *   pisa_block_heterogeneity           ("Covariance-Aware Block Selection": log(M_j + eps))
  *   pisa_attention     Alg. 1 lines 4-23 (Phase 1 exact, Phase 2 zeroth-order scan,
  *                                       Phase 3 global first-order term, one online softmax)
  *   dense_attention    Preliminaries, first equation (softmax(QK^T/sqrt d)V), the
@@ -43,6 +44,7 @@ enum {
 };
 
 enum { PISA_FP32 = 0, PISA_BF16 = 1 };
+enum { PISA_NORM_SPECTRAL = 0, PISA_NORM_FROBENIUS = 1 };
 
 typedef struct pisa_shape {
   int32_t batch;      /* >= 1 */
@@ -62,7 +64,8 @@ int32_t pisa_num_blocks(int32_t seq_len, int32_t block);
  * k = N - floor(r*N + 1e-9), clamped to [0, N].  Returns -1 if N < 0 or r is NaN. */
 int32_t pisa_topk_count(int32_t num_blocks, double sparsity);
 
-/* Bytes of device scratch that pisa_block_stats, pisa_select and pisa_attention each need
+/* Bytes of device scratch that pisa_block_stats, pisa_block_heterogeneity, pisa_select and
+ * pisa_attention each need
  * for this shape (the largest of: partial sums of H, reduced in a fixed order so the result
  * is run-to-run identical; the N x N fp64 pooled logits per head; the bf16 centroid tiles
  * and the packed hsum the attention kernel streams).  One buffer of this size serves all
@@ -88,10 +91,29 @@ int32_t pisa_block_stats(const pisa_shape* shape, const void* q, const void* k, 
                          void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Methodology, "Covariance-Aware Block Selection": per key block j the heterogeneity
+ *   M_j = || H_j - Hbar ||,  H_j = sum_n (k_{j,n} - kbar_j)^T v_{j,n},  Hbar = (1/N) sum_j H_j,
+ * and the column bias log(M_j + eps) that the selection score adds to the pooled logit.
+ *   norm_kind  PISA_NORM_SPECTRAL: operator 2-norm (the norm of the paper's error analysis),
+ *              by 48 power-iteration steps on (H_j - Hbar)^T (H_j - Hbar) from a fixed start
+ *              vector: a lower bound that, for the nearly flat spectra of these rank-<=B
+ *              matrices, can stop a few percent short of the exact value;
+ *              PISA_NORM_FROBENIUS: exact (fp64), cheaper, an upper bound of the spectral norm.
+ *   kbar64     fp64 [batch,heads,N,d] as written by pisa_block_stats
+ *   log_m      fp64 [batch,heads,N], written
+ * All arithmetic is fp64.  `workspace` must hold pisa_workspace_bytes(shape).
+ * The paper enables this score for image models only; pass log_m as `col_bias` to pisa_select.
+ */
+int32_t pisa_block_heterogeneity(const pisa_shape* shape, const void* k, const void* v,
+                                 const double* kbar64, int32_t norm_kind, double eps, double* log_m,
+                                 void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Alg. 1 line 2.  For every (batch, head, query block i): logits z_ij = s * qbar_i . kbar_j
- * (the selection-score equation without its covariance term; softmax is monotone so the
- * logits are ranked directly), and the k_top largest are kept; equal logits go to the lower
- * block index.
+ * (+ col_bias[j] if given: the selection-score equation with or without its covariance term;
+ * softmax is monotone so the logits are ranked directly), and the k_top largest are kept;
+ * equal logits go to the lower block index.
+ *   col_bias fp64 [batch,heads,N] or NULL
  *   idx      int32 [batch,heads,N,k_top], ascending and unique within a row
  *   kth_gap  fp32  [batch,heads,N]: z of rank k_top minus z of rank k_top+1 (+inf when
  *            k_top is 0 or N); may be NULL.  Rows with a tiny gap are the only ones where
@@ -100,7 +122,7 @@ int32_t pisa_block_stats(const pisa_shape* shape, const void* q, const void* k, 
  * `workspace` must hold pisa_workspace_bytes(shape); its contents are overwritten.
  */
 int32_t pisa_select(const pisa_shape* shape, const double* qbar64, const double* kbar64,
-                    int32_t k_top, int32_t* idx, float* kth_gap,
+                    const double* col_bias, int32_t k_top, int32_t* idx, float* kth_gap,
                     void* workspace, size_t workspace_bytes, void* stream);
 
 /*

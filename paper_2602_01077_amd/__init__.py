@@ -19,9 +19,10 @@ LIB_PATH = os.path.join(_PKG_DIR, "libpisa.so")
 
 PISA_OK, PISA_INVALID_ARG, PISA_UNSUPPORTED, PISA_WORKSPACE_TOO_SMALL, PISA_HIP_ERROR = range(5)
 PISA_FP32, PISA_BF16 = 0, 1
+PISA_NORM_SPECTRAL, PISA_NORM_FROBENIUS = 0, 1
 
 EXPORTS = ("pisa_num_blocks", "pisa_topk_count", "pisa_workspace_bytes", "pisa_block_stats",
-           "pisa_select", "pisa_attention", "dense_attention", "pisa_last_error")
+           "pisa_block_heterogeneity", "pisa_select", "pisa_attention", "dense_attention", "pisa_last_error")
 
 
 class PisaShape(ctypes.Structure):
@@ -53,7 +54,9 @@ def _load() -> ctypes.CDLL:
     lib.pisa_workspace_bytes.restype = sz
     lib.pisa_block_stats.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.pisa_block_stats.restype = i32
-    lib.pisa_select.argtypes = [shp, vp, vp, i32, vp, vp, vp, sz, vp]
+    lib.pisa_block_heterogeneity.argtypes = [shp, vp, vp, vp, i32, ctypes.c_double, vp, vp, sz, vp]
+    lib.pisa_block_heterogeneity.restype = i32
+    lib.pisa_select.argtypes = [shp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
     lib.pisa_select.restype = i32
     lib.pisa_attention.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
     lib.pisa_attention.restype = i32
@@ -164,22 +167,36 @@ def block_stats_into(shape, q, k, v, out: dict, workspace: torch.Tensor) -> None
         _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream()))
 
 
+def block_heterogeneity(shape: PisaShape, k, v, kbar64, norm: int = PISA_NORM_SPECTRAL, eps: float = 1e-6,
+                        workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """pisa_block_heterogeneity.  Returns log(M_j + eps), fp64 [b,h,N]."""
+    b, h, n, _ = kbar64.shape
+    log_m = torch.empty(b, h, n, dtype=torch.float64, device=k.device)
+    ws = alloc_workspace(shape, k.device) if workspace is None else workspace
+    _check(_lib.pisa_block_heterogeneity(
+        ctypes.byref(shape), _dev(k, "k"), _dev(v, "v", like=k), _dev(kbar64, "kbar64", torch.float64),
+        norm, float(eps), _dev(log_m, "log_m", torch.float64),
+        _dev(ws, "workspace"), ws.numel() * ws.element_size(), _stream()))
+    return log_m
+
+
 def select(shape: PisaShape, qbar64, kbar64, k_top: int, workspace: Optional[torch.Tensor] = None,
-           want_gap: bool = True) -> Tuple[torch.Tensor, Optional[torch.Tensor]]:
+           want_gap: bool = True, col_bias: Optional[torch.Tensor] = None
+           ) -> Tuple[torch.Tensor, Optional[torch.Tensor]]:
     """pisa_select.  Returns (idx int32 [b,h,N,k_top], kth_gap fp32 [b,h,N] or None)."""
     b, h, n, _ = qbar64.shape
     dev = qbar64.device
     idx = torch.empty(b, h, n, k_top, dtype=torch.int32, device=dev)
     gap = torch.empty(b, h, n, dtype=torch.float32, device=dev) if want_gap else None
     ws = alloc_workspace(shape, dev) if workspace is None else workspace
-    select_into(shape, qbar64, kbar64, k_top, idx, gap, ws)
+    select_into(shape, qbar64, kbar64, k_top, idx, gap, ws, col_bias)
     return idx, gap
 
 
-def select_into(shape, qbar64, kbar64, k_top: int, idx, gap, workspace) -> None:
+def select_into(shape, qbar64, kbar64, k_top: int, idx, gap, workspace, col_bias=None) -> None:
     _check(_lib.pisa_select(
         ctypes.byref(shape), _dev(qbar64, "qbar64", torch.float64), _dev(kbar64, "kbar64", torch.float64),
-        k_top, _dev(idx, "idx", torch.int32) if k_top > 0 else None, _dev(gap, "kth_gap", torch.float32),
+        _dev(col_bias, "col_bias", torch.float64), k_top, _dev(idx, "idx", torch.int32) if k_top > 0 else None, _dev(gap, "kth_gap", torch.float32),
         _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream()))
 
 
@@ -219,20 +236,23 @@ def dense_attention(q, k, v, block: int = 64, scale: Optional[float] = None,
 
 
 def pisa_forward(q, k, v, block: int = 64, sparsity: float = 0.85, first_order: bool = True,
-                 want_lse: bool = False, approximate: bool = True):
+                 want_lse: bool = False, approximate: bool = True, covariance_aware: bool = False,
+                 norm: int = PISA_NORM_SPECTRAL, eps: float = 1e-6):
     """The whole hot path: block_stats -> select -> attention.
 
     first_order=False gives the zeroth-order variant, approximate=False plain block-sparse
-    attention over the selected blocks.  Returns dict(out, lse, idx, kth_gap, stats, k_top).
+    attention over the selected blocks, covariance_aware=True adds log(M_j + eps) to the
+    selection score.  Returns dict(out, lse, idx, kth_gap, stats, k_top, log_m).
     """
     shape = make_shape(q, block)
     n = num_blocks(q.shape[2], block)
     k_top = topk_count(n, sparsity)
     ws = alloc_workspace(shape, q.device)
     stats = block_stats(q, k, v, block, ws)
-    idx, gap = select(shape, stats["qbar64"], stats["kbar64"], k_top, ws)
+    log_m = block_heterogeneity(shape, k, v, stats["kbar64"], norm, eps, ws) if covariance_aware else None
+    idx, gap = select(shape, stats["qbar64"], stats["kbar64"], k_top, ws, col_bias=log_m)
     out, lse = attention(shape, q, k, v, stats["kbar"] if approximate else None,
                          stats["vsum"] if approximate else None,
                          stats["hsum"] if (first_order and approximate) else None, idx, k_top,
                          want_lse=want_lse, workspace=ws)
-    return dict(out=out, lse=lse, idx=idx, kth_gap=gap, stats=stats, k_top=k_top)
+    return dict(out=out, lse=lse, idx=idx, kth_gap=gap, stats=stats, k_top=k_top, log_m=log_m)

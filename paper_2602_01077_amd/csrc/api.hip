@@ -93,7 +93,8 @@ int32_t pisa_topk_count(int32_t num_blocks, double sparsity) {
 size_t pisa_workspace_bytes(const pisa_shape* shape) {
   Dims dm;
   if (resolve(shape, &dm) != PISA_OK) return 0;
-  return std::max({stats_workspace_bytes(dm), select_workspace_bytes(dm), attention_workspace_bytes(dm)});
+  return std::max({stats_workspace_bytes(dm), select_workspace_bytes(dm), attention_workspace_bytes(dm),
+                   hetero_workspace_bytes(dm)});
 }
 
 int32_t pisa_block_stats(const pisa_shape* shape, const void* q, const void* k, const void* v,
@@ -116,8 +117,29 @@ int32_t pisa_block_stats(const pisa_shape* shape, const void* q, const void* k, 
   return PISA_OK;
 }
 
+int32_t pisa_block_heterogeneity(const pisa_shape* shape, const void* k, const void* v,
+                                 const double* kbar64, int32_t norm_kind, double eps, double* log_m,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+  Dims dm;
+  int32_t rc = resolve(shape, &dm);
+  if (rc != PISA_OK) return rc;
+  if (!k || !v || !kbar64 || !log_m) return fail(PISA_INVALID_ARG, "k, v, kbar64, log_m must not be NULL");
+  if (norm_kind != PISA_NORM_SPECTRAL && norm_kind != PISA_NORM_FROBENIUS)
+    return fail(PISA_INVALID_ARG, "norm_kind must be PISA_NORM_SPECTRAL (0) or PISA_NORM_FROBENIUS (1)");
+  if (!(eps >= 0.0)) return fail(PISA_INVALID_ARG, "eps must be >= 0");
+  size_t need = hetero_workspace_bytes(dm);
+  if (!workspace) return fail(PISA_INVALID_ARG, "workspace is NULL (need %zu bytes)", need);
+  if (workspace_bytes < need)
+    return fail(PISA_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, need %zu", workspace_bytes, need);
+  hipError_t e = launch_block_heterogeneity(dm, k, v, kbar64, norm_kind == PISA_NORM_SPECTRAL,
+                                            kPowerIterations, eps, log_m, (double*)workspace,
+                                            (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail("pisa_block_heterogeneity", e);
+  return PISA_OK;
+}
+
 int32_t pisa_select(const pisa_shape* shape, const double* qbar64, const double* kbar64,
-                    int32_t k_top, int32_t* idx, float* kth_gap,
+                    const double* col_bias, int32_t k_top, int32_t* idx, float* kth_gap,
                     void* workspace, size_t workspace_bytes, void* stream) {
   Dims dm;
   int32_t rc = resolve(shape, &dm);
@@ -132,7 +154,7 @@ int32_t pisa_select(const pisa_shape* shape, const double* qbar64, const double*
   if (!workspace) return fail(PISA_INVALID_ARG, "workspace is NULL (need %zu bytes)", need);
   if (workspace_bytes < need)
     return fail(PISA_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, need %zu", workspace_bytes, need);
-  hipError_t e = launch_select(dm, qbar64, kbar64, k_top, idx, kth_gap, (double*)workspace,
+  hipError_t e = launch_select(dm, qbar64, kbar64, col_bias, k_top, idx, kth_gap, (double*)workspace,
                                (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail("pisa_select", e);
   return PISA_OK;

@@ -22,6 +22,8 @@ struct Dims {
 constexpr int kTile = 64;
 // Largest block count the selection and the Phase-2 column mask are sized for.
 constexpr int kMaxBlocks = 4096;
+// Power-iteration steps (on D^T D) for the spectral norm of the block heterogeneity.
+constexpr int kPowerIterations = 48;
 
 // Records the message returned by pisa_last_error() and returns `code`.
 int32_t fail(int32_t code, const char* fmt, ...);
@@ -41,8 +43,13 @@ hipError_t launch_block_stats(const Dims& dm, const void* q, const void* k, cons
                               double* qbar64, double* kbar64, float* partial_h,
                               hipStream_t stream);
 size_t select_workspace_bytes(const Dims& dm);
-hipError_t launch_select(const Dims& dm, const double* qbar64, const double* kbar64, int k_top,
-                         int32_t* idx, float* kth_gap, double* zbuf, hipStream_t stream);
+hipError_t launch_select(const Dims& dm, const double* qbar64, const double* kbar64,
+                         const double* col_bias, int k_top, int32_t* idx, float* kth_gap, double* zbuf,
+                         hipStream_t stream);
+size_t hetero_workspace_bytes(const Dims& dm);
+hipError_t launch_block_heterogeneity(const Dims& dm, const void* k, const void* v, const double* kbar64,
+                                      int spectral, int n_iter, double eps, double* log_m,
+                                      double* workspace, hipStream_t stream);
 
 // Arguments of the attention kernels (dense and PISA share them).
 struct AttnArgs {

@@ -1,4 +1,5 @@
-// pisa_select: pooled block logits and top-k per query block (Alg. 1 line 2).
+// pisa_select: pooled block logits and top-k per query block (Alg. 1 line 2), with the
+// optional log(M_j + eps) column bias of the covariance-aware score.
 //
 // Two kernels.  (1) fp64 logits z[bh][i][j] = s * qbar_i . kbar_j, register-tiled
 // on the vector ALUs, written to scratch.  (2) One workgroup per row: an MSB-first
@@ -13,8 +14,10 @@ namespace {
 constexpr int kZT = 64;   // logits tile edge
 constexpr int kZC = 16;   // channels staged per step
 
+// col_bias (optional): [bh][N], added to every logit of key block j (covariance-aware score).
 __global__ __launch_bounds__(256) void logits_kernel(const double* __restrict__ qbar64,
                                                      const double* __restrict__ kbar64,
+                                                     const double* __restrict__ col_bias,
                                                      double* __restrict__ z, int N, int D, double scale) {
   __shared__ double qs[kZC][kZT + 1];
   __shared__ double ks[kZC][kZT + 1];
@@ -61,7 +64,7 @@ __global__ __launch_bounds__(256) void logits_kernel(const double* __restrict__ 
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
       const int j = j0 + tj * 4 + b;
-      if (j < N) zb[(size_t)i * N + j] = scale * acc[a][b];
+      if (j < N) zb[(size_t)i * N + j] = scale * acc[a][b] + (col_bias ? col_bias[bh * N + j] : 0.0);
     }
   }
 }
@@ -199,11 +202,12 @@ size_t select_workspace_bytes(const Dims& dm) {
   return (size_t)dm.bh() * dm.N * dm.N * sizeof(double);
 }
 
-hipError_t launch_select(const Dims& dm, const double* qbar64, const double* kbar64, int k_top,
-                         int32_t* idx, float* kth_gap, double* zbuf, hipStream_t stream) {
+hipError_t launch_select(const Dims& dm, const double* qbar64, const double* kbar64,
+                         const double* col_bias, int k_top, int32_t* idx, float* kth_gap, double* zbuf,
+                         hipStream_t stream) {
   const int nt = (dm.N + kZT - 1) / kZT;
-  hipLaunchKernelGGL(logits_kernel, dim3(nt, nt, dm.bh()), dim3(256), 0, stream, qbar64, kbar64, zbuf,
-                     dm.N, dm.d, (double)dm.scale);
+  hipLaunchKernelGGL(logits_kernel, dim3(nt, nt, dm.bh()), dim3(256), 0, stream, qbar64, kbar64, col_bias,
+                     zbuf, dm.N, dm.d, (double)dm.scale);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(topk_kernel, dim3(dm.N, dm.bh()), dim3(256), (size_t)dm.N * 8, stream, zbuf,

@@ -73,7 +73,8 @@ def test_bad_shapes_are_rejected(kw, code):
     assert lib.dense_attention(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, None, None) == code
     assert pisa.last_error() != ""
     assert lib.pisa_attention(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 1, FAKE, None, FAKE, 1 << 40, None) == code
-    assert lib.pisa_select(ctypes.byref(s), FAKE, FAKE, 1, FAKE, None, FAKE, 1 << 40, None) == code
+    assert lib.pisa_select(ctypes.byref(s), FAKE, FAKE, None, 1, FAKE, None, FAKE, 1 << 40, None) == code
+    assert lib.pisa_block_heterogeneity(ctypes.byref(s), FAKE, FAKE, FAKE, 0, 1e-6, FAKE, FAKE, 1 << 40, None) == code
     assert lib.pisa_block_stats(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE,
                                 FAKE, 1 << 40, None) == code
 
@@ -92,16 +93,22 @@ def test_null_and_range_arguments():
         == pisa.PISA_INVALID_ARG          # kbar without vsum
     assert lib.pisa_attention(ctypes.byref(s), FAKE, FAKE, FAKE, None, None, None, None, 0, FAKE, None, FAKE, 1 << 40, None) \
         == pisa.PISA_INVALID_ARG          # keep-or-drop with no block kept
-    assert lib.pisa_select(ctypes.byref(s), FAKE, FAKE, -1, FAKE, None, FAKE, 1 << 40, None) == pisa.PISA_INVALID_ARG
-    assert lib.pisa_select(ctypes.byref(s), FAKE, FAKE, 4, FAKE, None, FAKE, 8, None) == pisa.PISA_WORKSPACE_TOO_SMALL
-    assert lib.pisa_select(ctypes.byref(s), FAKE, FAKE, 4, FAKE, None, None, 0, None) == pisa.PISA_INVALID_ARG
+    assert lib.pisa_select(ctypes.byref(s), FAKE, FAKE, None, -1, FAKE, None, FAKE, 1 << 40, None) == pisa.PISA_INVALID_ARG
+    assert lib.pisa_select(ctypes.byref(s), FAKE, FAKE, None, 4, FAKE, None, FAKE, 8, None) == pisa.PISA_WORKSPACE_TOO_SMALL
+    assert lib.pisa_select(ctypes.byref(s), FAKE, FAKE, None, 4, FAKE, None, None, 0, None) == pisa.PISA_INVALID_ARG
     assert lib.pisa_block_stats(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE,
                                 FAKE, 16, None) == pisa.PISA_WORKSPACE_TOO_SMALL
     assert "workspace" in pisa.last_error()
     assert lib.pisa_block_stats(ctypes.byref(s), FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE,
                                 FAKE, 1 << 40, None) == pisa.PISA_INVALID_ARG
+    assert lib.pisa_block_heterogeneity(ctypes.byref(s), FAKE, FAKE, FAKE, 5, 1e-6, FAKE, FAKE, 1 << 40, None) \
+        == pisa.PISA_INVALID_ARG
+    assert lib.pisa_block_heterogeneity(ctypes.byref(s), FAKE, FAKE, FAKE, 0, -1.0, FAKE, FAKE, 1 << 40, None) \
+        == pisa.PISA_INVALID_ARG
+    assert lib.pisa_block_heterogeneity(ctypes.byref(s), FAKE, FAKE, FAKE, 1, 1e-6, FAKE, FAKE, 64, None) \
+        == pisa.PISA_WORKSPACE_TOO_SMALL
     big = shape(seq_len=64 * 5000)
-    assert lib.pisa_select(ctypes.byref(big), FAKE, FAKE, 4, FAKE, None, FAKE, 1 << 60, None) == pisa.PISA_UNSUPPORTED
+    assert lib.pisa_select(ctypes.byref(big), FAKE, FAKE, None, 4, FAKE, None, FAKE, 1 << 60, None) == pisa.PISA_UNSUPPORTED
 
 
 def test_binding_refuses_host_tensors():

@@ -183,6 +183,52 @@ def test_all_blocks_selected_is_bitwise_dense(lib, dtype, d, B):
     assert torch.equal(res["lse"], lse)
 
 
+@pytest.mark.parametrize("dtype,d,B,L", [("bf16", 128, 64, 1500), ("bf16", 128, 128, 1400), ("fp32", 64, 64, 900)])
+def test_covariance_aware_selection(lib, dtype, d, B, L):
+    """Covariance-Aware Block Selection: log(M_j + eps) from pisa_block_heterogeneity (both
+    norms) against the oracle's per-block H_j, then pisa_select with that column bias."""
+    w = WORKLOADS["tiny"].with_(name="cov", heads=2, seq_len=L, head_dim=d, dtype=dtype, block=B,
+                                sparsity=0.75, seed=51)
+    q, k, v = make_qkv(w)
+    qd, kd, vd = q.to(DEV), k.to(DEV), v.to(DEV)
+    scale = lib.resolved_scale(d)
+    shape = lib.make_shape(qd, B)
+    st_gpu = lib.block_stats(qd, kd, vd, B)
+    N, k_top = w.num_blocks, w.topk
+    # Frobenius is exact (fp64); the spectral norm comes from 48 power-iteration steps, which
+    # approach the largest singular value from below and, for these nearly-flat spectra
+    # (rank <= block size, closely spaced singular values), stop a few percent short.
+    for norm, kind, tol in ((lib.PISA_NORM_FROBENIUS, "frobenius", 1e-9), (lib.PISA_NORM_SPECTRAL, "spectral", 5e-2)):
+        log_m = lib.block_heterogeneity(shape, kd, vd, st_gpu["kbar64"], norm, 1e-6)
+        idx, gap = lib.select(shape, st_gpu["qbar64"], st_gpu["kbar64"], k_top, col_bias=log_m)
+        torch.cuda.synchronize()
+        for h in range(w.heads):
+            Q, K, V = head_np(q, 0, h), head_np(k, 0, h), head_np(v, 0, h)
+            st = po.block_stats(Q, K, V, B, per_block_H=True)
+            M = po.block_heterogeneity(st["Hj"], st["hsum"], kind)
+            got = log_m[0, h].cpu().numpy()
+            assert np.abs(np.exp(got) - (M + 1e-6)).max() <= tol * M.max(), (kind, h)
+            if kind == "spectral":
+                assert np.all(np.exp(got) <= (M + 1e-6) * (1 + 1e-9)), "power iteration is a lower bound"
+            # the select stage is judged on the bias it was given ...
+            ref, gref = po.select(st["qbar"], st["kbar"], scale, k_top, col_bias=got)
+            check_select(idx[0, h].cpu().numpy(), gap[0, h].cpu().numpy().astype(np.float64), ref, gref, N,
+                         where=f" cov {kind} head {h}")
+            # ... and against the oracle's own bias it may differ only where the gap is within the norm's accuracy
+            ref2, gref2 = po.select(st["qbar"], st["kbar"], scale, k_top, col_bias=np.log(M + 1e-6))
+            diff = np.any(idx[0, h].cpu().numpy() != ref2, axis=1)
+            assert not np.any(diff & (gref2 > 2 * tol)), (kind, h)
+    # end to end with the covariance-aware score
+    res = lib.pisa_forward(qd, kd, vd, B, w.sparsity, covariance_aware=True, norm=lib.PISA_NORM_FROBENIUS)
+    torch.cuda.synchronize()
+    for h in range(w.heads):
+        Q, K, V = head_np(q, 0, h), head_np(k, 0, h), head_np(v, 0, h)
+        st = po.block_stats(Q, K, V, B)
+        ref, _ = po.attention_head(Q, K, V, B, res["idx"][0, h].cpu().numpy(), scale, "hybrid", stats=st)
+        rel, cos = row_errors(res["out"][0, h].float().cpu().numpy(), ref)
+        assert rel <= TOL[q.dtype] and cos >= COS_MIN
+
+
 def test_flux_config_full(lib):
     """FLUX.1-dev-shaped config (24 heads, N=4608, bf16, r=0.85) compared in full."""
     run_full_case(lib, WORKLOADS["flux"])
