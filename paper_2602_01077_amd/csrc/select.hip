@@ -1,71 +1,98 @@
 // pisa_select: pooled block logits and top-k per query block (Alg. 1 line 2), with the
 // optional log(M_j + eps) column bias of the covariance-aware score.
 //
-// Two kernels.  (1) fp64 logits z[bh][i][j] = s * qbar_i . kbar_j, register-tiled
-// on the vector ALUs, written to scratch.  (2) One workgroup per row: an MSB-first
-// radix select on order-preserving 64-bit keys finds the k-th largest logit, ties at
-// the threshold are granted to the lowest block indices, and the chosen indices are
-// compacted in ascending order with a prefix sum.
+// Two kernels.  (1) fp64 logits z[bh][i][j] = s * qbar_i . kbar_j on the fp64 matrix
+// cores, one wave per 64x64 tile, written to scratch.  (2) One WAVE per row, the row's
+// order-preserving 64-bit keys in registers: a bucket select narrows a key interval around
+// the k-th largest logit (256 buckets per level over the tightened [min, max] of the
+// surviving keys),
+// ties at the threshold are granted to the lowest block indices, and the chosen indices
+// are compacted in ascending order with wave ballots.  No workgroup barriers.
+#include <algorithm>
+
 #include "common.h"
 
 namespace pisa {
 namespace {
 
-constexpr int kZT = 64;   // logits tile edge
-constexpr int kZC = 16;   // channels staged per step
+typedef double f64x4 __attribute__((ext_vector_type(4)));
 
+constexpr int kZT = 64;   // logits tile edge (per wave)
+
+// v_mfma_f64_16x16x4_f64: lane l supplies A[l % 16][l / 16] and B[l / 16][l % 16]; register r
+// of the result holds D[4 * r + l / 16][l % 16].  A lane loads four consecutive channels
+// of its row at once and feeds them to four successive instructions: both operands use the
+// same channel for the same (instruction, l / 16), so the contraction covers every channel
+// exactly once.
 // col_bias (optional): [bh][N], added to every logit of key block j (covariance-aware score).
-__global__ __launch_bounds__(256) void logits_kernel(const double* __restrict__ qbar64,
-                                                     const double* __restrict__ kbar64,
-                                                     const double* __restrict__ col_bias,
-                                                     double* __restrict__ z, int N, int D, double scale) {
-  __shared__ double qs[kZC][kZT + 1];
-  __shared__ double ks[kZC][kZT + 1];
-  const int tid = threadIdx.x;
+template <int D>
+__global__ __launch_bounds__(256, 2) void logits_kernel(const double* __restrict__ qbar64,
+                                                        const double* __restrict__ kbar64,
+                                                        const double* __restrict__ col_bias,
+                                                        double* __restrict__ z, int N, double scale) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const size_t bh = blockIdx.z;
-  const int i0 = blockIdx.y * kZT, j0 = blockIdx.x * kZT;
+  const int i0 = blockIdx.y * kZT;
+  const int j0 = (blockIdx.x * 4 + wave) * kZT;
+  if (j0 >= N) return;                     // whole wave; the kernel has no barriers
+  const int r = lane & 15, kk = lane >> 4;
   const double* qb = qbar64 + bh * (size_t)N * D;
   const double* kb = kbar64 + bh * (size_t)N * D;
-  const int ti = tid / 16, tj = tid % 16;
-  double acc[4][4];
+  // Rows past N are clamped to N - 1: their products are computed and never stored.
+  const double* qp[4];
+  const double* kp[4];
+#pragma unroll
+  for (int a = 0; a < 4; ++a) {
+    qp[a] = qb + (size_t)min(i0 + 16 * a + r, N - 1) * D + 4 * kk;
+    kp[a] = kb + (size_t)min(j0 + 16 * a + r, N - 1) * D + 4 * kk;
+  }
+  f64x4 acc[4][4];
 #pragma unroll
   for (int a = 0; a < 4; ++a)
 #pragma unroll
-    for (int b = 0; b < 4; ++b) acc[a][b] = 0.0;
+    for (int b = 0; b < 4; ++b) acc[a][b] = f64x4{0.0, 0.0, 0.0, 0.0};
 
-  const int lr = tid / 4, lc = (tid % 4) * 4;   // loader: row, first channel of 4
-  for (int c0 = 0; c0 < D; c0 += kZC) {
+  f64x4 av[4], bv[4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int qi = i0 + lr, kj = j0 + lr;
-      qs[lc + u][lr] = qi < N ? qb[(size_t)qi * D + c0 + lc + u] : 0.0;
-      ks[lc + u][lr] = kj < N ? kb[(size_t)kj * D + c0 + lc + u] : 0.0;
+  for (int a = 0; a < 4; ++a) {
+    av[a] = *reinterpret_cast<const f64x4*>(qp[a]);
+    bv[a] = *reinterpret_cast<const f64x4*>(kp[a]);
+  }
+#pragma unroll 1
+  for (int c0 = 0; c0 < D; c0 += 16) {
+    f64x4 an[4], bn[4];
+    const int cn = c0 + 16 < D ? c0 + 16 : c0;      // last step reloads in place, unused
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+      an[a] = *reinterpret_cast<const f64x4*>(qp[a] + cn);
+      bn[a] = *reinterpret_cast<const f64x4*>(kp[a] + cn);
     }
-    __syncthreads();
 #pragma unroll
-    for (int c = 0; c < kZC; ++c) {
-      double qa[4], kk[4];
-#pragma unroll
-      for (int a = 0; a < 4; ++a) qa[a] = qs[c][ti * 4 + a];
-#pragma unroll
-      for (int b = 0; b < 4; ++b) kk[b] = ks[c][tj * 4 + b];
+    for (int u = 0; u < 4; ++u)
 #pragma unroll
       for (int a = 0; a < 4; ++a)
 #pragma unroll
-        for (int b = 0; b < 4; ++b) acc[a][b] = fma(qa[a], kk[b], acc[a][b]);
+        for (int b = 0; b < 4; ++b)
+          acc[a][b] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[a][u], bv[b][u], acc[a][b], 0, 0, 0);
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+      av[a] = an[a];
+      bv[a] = bn[a];
     }
-    __syncthreads();
   }
   double* zb = z + bh * (size_t)N * N;
 #pragma unroll
-  for (int a = 0; a < 4; ++a) {
-    const int i = i0 + ti * 4 + a;
-    if (i >= N) continue;
+  for (int b = 0; b < 4; ++b) {
+    const int j = j0 + 16 * b + r;
+    if (j >= N) continue;
+    const double bias = col_bias ? col_bias[bh * N + j] : 0.0;
 #pragma unroll
-    for (int b = 0; b < 4; ++b) {
-      const int j = j0 + tj * 4 + b;
-      if (j < N) zb[(size_t)i * N + j] = scale * acc[a][b] + (col_bias ? col_bias[bh * N + j] : 0.0);
-    }
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int i = i0 + 16 * a + 4 * e + kk;
+        if (i < N) zb[(size_t)i * N + j] = scale * acc[a][b][e] + bias;
+      }
   }
 }
 
@@ -78,121 +105,159 @@ __device__ inline double key_value(unsigned long long key) {
   return __longlong_as_double((long long)u);
 }
 
-// Exclusive prefix sum of one int per thread over a 256-thread workgroup.
-__device__ inline int block_exclusive_scan(int x, int* scratch /*[256]*/, int* total) {
-  const int tid = threadIdx.x;
-  scratch[tid] = x;
-  __syncthreads();
-  for (int off = 1; off < 256; off <<= 1) {
-    int add = tid >= off ? scratch[tid - off] : 0;
-    __syncthreads();
-    scratch[tid] += add;
-    __syncthreads();
+// Orders this wave's LDS traffic: writes before it are visible to every lane after it.
+__device__ inline void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+__device__ inline unsigned long long wave_min_u64(unsigned long long x) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    const unsigned long long y = __shfl_xor(x, off);
+    x = y < x ? y : x;
   }
-  const int incl = scratch[tid];
-  *total = scratch[255];
-  __syncthreads();
-  return incl - x;
+  return x;
+}
+__device__ inline unsigned long long wave_max_u64(unsigned long long x) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    const unsigned long long y = __shfl_xor(x, off);
+    x = y > x ? y : x;
+  }
+  return x;
+}
+__device__ inline int lanes_below(unsigned long long mask) {   // set bits of mask below this lane
+  return __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0u));
 }
 
-// One workgroup per (bh, query block i).  Dynamic LDS: N keys of 8 bytes.
+// One wave per (bh, query block i), four rows per workgroup.  Lane l holds keys l, l + 64, ...
+// in registers (KPL of them, so N <= 64 * KPL); LDS holds only the wave's 256-bin histogram.
+template <int KPL>
 __global__ __launch_bounds__(256) void topk_kernel(const double* __restrict__ z, int N, int k_top,
-                                                   int32_t* __restrict__ idx, float* __restrict__ kth_gap) {
-  extern __shared__ unsigned long long keys[];
-  __shared__ int hist[256];
-  __shared__ int scan_buf[256];
-  __shared__ unsigned long long s_prefix;
-  __shared__ int s_want;
-  __shared__ unsigned long long s_red[256];
-
-  const int tid = threadIdx.x;
-  const size_t row = (size_t)blockIdx.y * N + blockIdx.x;
-  const double* zr = z + row * (size_t)N;
-  for (int j = tid; j < N; j += 256) keys[j] = order_key(zr[j]);
-  if (tid == 0) {
-    s_prefix = 0ull;
-    s_want = k_top;
-  }
-  __syncthreads();
+                                                   size_t n_rows, int32_t* __restrict__ idx,
+                                                   float* __restrict__ kth_gap) {
+  __shared__ int hist_all[4][256];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const size_t row = (size_t)blockIdx.x * 4 + wave;
+  if (row >= n_rows) return;               // whole wave; the kernel has no workgroup barriers
+  int* hist = hist_all[wave];
+  int32_t* out = idx + row * (size_t)k_top;
 
   if (k_top == 0 || k_top == N) {
-    for (int j = tid; j < k_top; j += 256) idx[row * (size_t)k_top + j] = j;
-    if (kth_gap && tid == 0) kth_gap[row] = __int_as_float(0x7f800000);
+    for (int j = lane; j < k_top; j += 64) out[j] = j;
+    if (kth_gap && lane == 0) kth_gap[row] = __int_as_float(0x7f800000);
     return;
   }
-
-  // ---- radix select: key of rank k_top (1-based, descending) ----
-  for (int shift = 56; shift >= 0; shift -= 8) {
-    hist[tid] = 0;
-    __syncthreads();
-    const unsigned long long prefix = s_prefix;
-    const unsigned long long himask = shift == 56 ? 0ull : (~0ull << (shift + 8));
-    for (int j = tid; j < N; j += 256) {
-      const unsigned long long key = keys[j];
-      if ((key & himask) == prefix) atomicAdd(&hist[(int)((key >> shift) & 0xff)], 1);
-    }
-    __syncthreads();
-    // Wave 0 walks the 256 bins from the top: lane l owns bins 255-4l .. 252-4l, a wave
-    // prefix sum over the per-lane totals finds the lane, then the lane finds its bin.
-    if (tid < 64) {
-      const int want = s_want;
-      const int b0 = 255 - 4 * tid;
-      const int c0 = hist[b0], c1 = hist[b0 - 1], c2 = hist[b0 - 2], c3 = hist[b0 - 3];
-      const int mine = c0 + c1 + c2 + c3;
-      int incl = mine;
+  const double* zr = z + row * (size_t)N;
+  unsigned long long key[KPL];
 #pragma unroll
-      for (int off = 1; off < 64; off <<= 1) {
-        const int up = __shfl_up(incl, off);
-        if (tid >= off) incl += up;
-      }
-      const int before = incl - mine;               // keys in bins above this lane's bins
-      if (before < want && want <= incl) {          // exactly one lane
-        int w = want - before, digit = b0;
-        if (w > c0) { w -= c0; digit = b0 - 1;
-          if (w > c1) { w -= c1; digit = b0 - 2;
-            if (w > c2) { w -= c2; digit = b0 - 3; } } }
-        s_want = w;
-        s_prefix = prefix | ((unsigned long long)digit << shift);
-      }
-    }
-    __syncthreads();
-  }
-  const unsigned long long thr = s_prefix;   // the k-th largest key
-  const int take_equal = s_want;             // how many keys equal to thr are selected
+  for (int u = 0; u < KPL; ++u) key[u] = order_key(zr[min(lane + 64 * u, N - 1)]);
+  const int n_mine = (N - lane + 63) / 64;       // slots u < n_mine hold keys of this row
 
-  // ---- ascending compaction: each thread owns a contiguous index range ----
-  const int per = (N + 255) / 256;
-  const int lo = min(N, tid * per), hi = min(N, lo + per);
-  int n_eq = 0;
-  for (int j = lo; j < hi; ++j) n_eq += keys[j] == thr;
-  int total;
-  const int eq_base = block_exclusive_scan(n_eq, scan_buf, &total);
-  int n_sel = 0, eq_seen = eq_base;
-  for (int j = lo; j < hi; ++j) {
-    const unsigned long long key = keys[j];
-    if (key > thr) ++n_sel;
-    else if (key == thr) n_sel += (eq_seen++ < take_equal);
+  // ---- narrow [lo, hi] around the key of rank `want` (1-based, descending) among the keys
+  // inside it.  Each level re-centres 256 buckets on the surviving keys' own [min, max], so
+  // the shared sign / exponent bits of a row never produce a level that separates nothing.
+  unsigned long long lo = 0ull, hi = ~0ull;
+  int want = k_top;
+  {  // split by sign first: mixed signs would put a whole row into two or three buckets
+    int n_nonneg = 0;
+#pragma unroll
+    for (int u = 0; u < KPL; ++u)
+      n_nonneg += __builtin_popcountll(__ballot(u < n_mine && (key[u] >> 63) != 0ull));
+    if (want <= n_nonneg) {
+      lo = 1ull << 63;
+    } else {
+      want -= n_nonneg;
+      hi = (1ull << 63) - 1ull;
+    }
   }
-  const int out_base = block_exclusive_scan(n_sel, scan_buf, &total);
-  int32_t* out = idx + row * (size_t)k_top;
-  int w = out_base;
-  eq_seen = eq_base;
-  unsigned long long best_unsel = 0ull;       // largest key left out (keys are never 0 for finite z)
-  for (int j = lo; j < hi; ++j) {
-    const unsigned long long key = keys[j];
-    bool sel = key > thr;
-    if (key == thr) sel = (eq_seen++ < take_equal);
-    if (sel) out[w++] = j;
-    else best_unsel = key > best_unsel ? key : best_unsel;
+  unsigned long long thr;                  // the k-th largest key
+  int take_equal;                          // how many keys equal to thr are selected
+  for (;;) {
+    unsigned long long kmin = ~0ull, kmax = 0ull;
+#pragma unroll
+    for (int u = 0; u < KPL; ++u)
+      if (u < n_mine && key[u] >= lo && key[u] <= hi) {
+        kmin = key[u] < kmin ? key[u] : kmin;
+        kmax = key[u] > kmax ? key[u] : kmax;
+      }
+    kmin = wave_min_u64(kmin);
+    kmax = wave_max_u64(kmax);
+    const unsigned long long range = kmax - kmin;
+    if (range == 0ull) {                   // every surviving key is the same value
+      thr = kmin;
+      take_equal = want;
+      break;
+    }
+    const int sh = max(0, 56 - (int)__builtin_clzll(range));     // (range >> sh) <= 255
+    reinterpret_cast<int4*>(hist)[lane] = make_int4(0, 0, 0, 0);
+    wave_lds_sync();
+#pragma unroll
+    for (int u = 0; u < KPL; ++u)
+      if (u < n_mine && key[u] >= kmin && key[u] <= kmax)
+        atomicAdd(&hist[(int)((key[u] - kmin) >> sh)], 1);
+    wave_lds_sync();
+    // Walk the buckets from the top: lane l owns buckets 255-4l .. 252-4l; a wave prefix
+    // sum over the per-lane totals finds the lane, then the lane finds its bucket.
+    const int4 c = reinterpret_cast<const int4*>(hist)[63 - lane];   // c.w = bucket 255-4l
+    const int mine = c.x + c.y + c.z + c.w;
+    int incl = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int up = __shfl_up(incl, off);
+      if (lane >= off) incl += up;
+    }
+    const int before = incl - mine;        // keys in buckets above this lane's buckets
+    const bool found = before < want && want <= incl;              // exactly one lane
+    int w = want - before, bucket = 255 - 4 * lane, cnt = c.w;
+    if (w > c.w) { w -= c.w; bucket -= 1; cnt = c.z;
+      if (w > c.z) { w -= c.z; bucket -= 1; cnt = c.y;
+        if (w > c.y) { w -= c.y; bucket -= 1; cnt = c.x; } } }
+    const int src = __builtin_ctzll(__ballot(found));
+    w = __shfl(w, src);
+    bucket = __shfl(bucket, src);
+    cnt = __shfl(cnt, src);
+    wave_lds_sync();                       // histogram reads done before the next level clears it
+    lo = kmin + ((unsigned long long)bucket << sh);
+    const unsigned long long span = sh == 0 ? 0ull : (1ull << sh) - 1ull;
+    hi = lo > ~0ull - span ? ~0ull : lo + span;
+    want = w;
+    if (cnt == want) {                     // the whole bucket is selected: keys >= lo
+      thr = lo;
+      take_equal = 0x7fffffff;
+      break;
+    }
+    if (sh == 0) {                         // a bucket is one key value: ties at the threshold
+      thr = lo;
+      take_equal = want;
+      break;
+    }
+  }
+
+  // ---- ascending compaction, 64 consecutive indices per step ----
+  int base = 0, eq_seen = 0;
+  unsigned long long min_sel = ~0ull, max_unsel = 0ull;   // keys are never 0 for finite z
+#pragma unroll
+  for (int u = 0; u < KPL; ++u) {
+    const bool valid = u < n_mine;
+    const bool eq = valid && key[u] == thr;
+    const unsigned long long eq_mask = __ballot(eq);
+    const bool sel = valid && (key[u] > thr || (eq && eq_seen + lanes_below(eq_mask) < take_equal));
+    const unsigned long long sel_mask = __ballot(sel);
+    if (sel) {
+      out[base + lanes_below(sel_mask)] = lane + 64 * u;
+      min_sel = key[u] < min_sel ? key[u] : min_sel;
+    } else if (valid) {
+      max_unsel = key[u] > max_unsel ? key[u] : max_unsel;
+    }
+    base += __builtin_popcountll(sel_mask);
+    eq_seen += __builtin_popcountll(eq_mask);
   }
   if (kth_gap) {
-    s_red[tid] = best_unsel;
-    __syncthreads();
-    for (int off = 128; off > 0; off >>= 1) {
-      if (tid < off) s_red[tid] = s_red[tid] > s_red[tid + off] ? s_red[tid] : s_red[tid + off];
-      __syncthreads();
-    }
-    if (tid == 0) kth_gap[row] = (float)(key_value(thr) - key_value(s_red[0]));
+    min_sel = wave_min_u64(min_sel);
+    max_unsel = wave_max_u64(max_unsel);
+    if (lane == 0) kth_gap[row] = (float)(key_value(min_sel) - key_value(max_unsel));
   }
 }
 
@@ -206,12 +271,25 @@ hipError_t launch_select(const Dims& dm, const double* qbar64, const double* kba
                          const double* col_bias, int k_top, int32_t* idx, float* kth_gap, double* zbuf,
                          hipStream_t stream) {
   const int nt = (dm.N + kZT - 1) / kZT;
-  hipLaunchKernelGGL(logits_kernel, dim3(nt, nt, dm.bh()), dim3(256), 0, stream, qbar64, kbar64, col_bias,
-                     zbuf, dm.N, dm.d, (double)dm.scale);
+  const dim3 zgrid((nt + 3) / 4, nt, dm.bh());
+  if (dm.d == 64)
+    hipLaunchKernelGGL(logits_kernel<64>, zgrid, dim3(256), 0, stream, qbar64, kbar64, col_bias, zbuf, dm.N,
+                       (double)dm.scale);
+  else
+    hipLaunchKernelGGL(logits_kernel<128>, zgrid, dim3(256), 0, stream, qbar64, kbar64, col_bias, zbuf, dm.N,
+                       (double)dm.scale);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(topk_kernel, dim3(dm.N, dm.bh()), dim3(256), (size_t)dm.N * 8, stream, zbuf,
-                     dm.N, k_top, idx, kth_gap);
+  const size_t n_rows = (size_t)dm.bh() * dm.N;
+  const dim3 grid((unsigned)((n_rows + 3) / 4));
+  if (dm.N <= 64 * 8)
+    hipLaunchKernelGGL(topk_kernel<8>, grid, dim3(256), 0, stream, zbuf, dm.N, k_top, n_rows, idx, kth_gap);
+  else if (dm.N <= 64 * 20)
+    hipLaunchKernelGGL(topk_kernel<20>, grid, dim3(256), 0, stream, zbuf, dm.N, k_top, n_rows, idx, kth_gap);
+  else if (dm.N <= 64 * 32)
+    hipLaunchKernelGGL(topk_kernel<32>, grid, dim3(256), 0, stream, zbuf, dm.N, k_top, n_rows, idx, kth_gap);
+  else
+    hipLaunchKernelGGL(topk_kernel<64>, grid, dim3(256), 0, stream, zbuf, dm.N, k_top, n_rows, idx, kth_gap);
   return hipGetLastError();
 }
 

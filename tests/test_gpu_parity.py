@@ -273,6 +273,51 @@ def test_select_ties_and_duplicates(lib):
             assert np.abs(gap[0, h].cpu().numpy() - gref).max() < 1e-5
 
 
+@pytest.mark.parametrize("N", [65, 512, 513, 1280, 1281, 2049, 4096])
+def test_select_all_sizes_and_degenerate_rows(lib, N):
+    """pisa_select alone, at block counts on both sides of every keys-per-lane build of the
+    top-k kernel (up to the 4096-block maximum), on rows built to hit its special paths:
+    one sign only, a constant row, a row of two values, duplicates at the threshold, a huge
+    dynamic range, and a column bias."""
+    d, H = 64, 2
+    rng = np.random.default_rng(N)
+    qb = rng.standard_normal((1, H, N, d))
+    kb = rng.standard_normal((1, H, N, d))
+    qb[0, 0, 1] = 0.0                                   # constant row: every logit 0 (then the bias)
+    kb[0, 0, 5] = kb[0, 0, 2]                           # duplicate columns
+    kb[0, 0, N - 1] = kb[0, 0, 2]
+    kb[0, 1, : N // 2] = kb[0, 1, 0]                    # half of the columns identical
+    kb[0, 1, N // 2:] = -kb[0, 1, 0]                    # ... the other half their negation: two values per row
+    qb[0, 0, 3] *= 1e150                                # huge magnitudes
+    qb[0, 0, 4] *= 1e-150                               # tiny magnitudes
+    bias = rng.standard_normal((1, H, N)) * 3.0
+    bias[0, 0, 7] = 1e6                                 # one column always chosen
+    bias[0, 1] = 0.0
+    shape = lib.PisaShape(1, H, N * 64, d, 64, lib.PISA_FP32, 0.0)
+    scale = lib.resolved_scale(d)
+    ws = lib.alloc_workspace(shape, DEV)
+    qd, kd, bd = (torch.from_numpy(x).to(DEV) for x in (qb, kb, bias))
+    for k_top in sorted({1, 2, N // 7, N // 2, N - 1}):
+        for use_bias in (False, True):
+            idx, gap = lib.select(shape, qd, kd, k_top, ws, col_bias=bd if use_bias else None)
+            torch.cuda.synchronize()
+            for h in range(H):
+                cb = bias[0, h] if use_bias else None
+                ref, gref = po.select(qb[0, h], kb[0, h], scale, k_top, col_bias=cb)
+                z = po.pooled_logits(qb[0, h], kb[0, h], scale) + (0.0 if cb is None else cb[None, :])
+                got = idx[0, h].cpu().numpy()
+                check_index_rows_valid(got, N)
+                bad = np.nonzero(np.any(got != ref, axis=1))[0]
+                for i in bad:
+                    # legal only where fp64 rounding of z itself reorders near-equal logits
+                    scale_i = max(1.0, np.abs(z[i]).max())
+                    assert np.allclose(np.sort(z[i, got[i]]), np.sort(z[i, ref[i]]), rtol=0, atol=1e-12 * scale_i), \
+                        (N, k_top, use_bias, h, int(i))
+                g = gap[0, h].cpu().numpy().astype(np.float64)
+                ok = np.isfinite(gref) & (np.abs(gref) < 1e30)
+                assert np.all(np.abs(g[ok] - gref[ok]) <= 1e-5 * np.maximum(1.0, np.abs(gref[ok]))), (N, k_top, h)
+
+
 def _sampled_blocks(w, rng, extra=()):
     N = w.num_blocks
     fixed = {0, N - 1, *extra}
