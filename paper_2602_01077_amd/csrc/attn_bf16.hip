@@ -25,7 +25,7 @@
 // key blocks in ascending order (bit scan over two LDS bitmasks); a tile selected by only
 // one block is skipped by the other block's waves.  Every shared tile halves the L2->LDS
 // traffic per flop.  Phase 2 streams bf16 centroid tiles prepared by a small pre-pass
-// (kbar split into hi + lo parts so centroid logits keep fp32-level accuracy; vsum / B_j;
+// (kbar_j rounded to bf16, the precision the keys themselves arrive in; vsum_j / B_j;
 // log2 B_j), Phase 3 multiplies by the pre-packed hi/lo split of hsum.
 #include <type_traits>
 
@@ -57,8 +57,7 @@ struct PB {
   const __bf16* q;
   const __bf16* k;
   const __bf16* v;
-  const __bf16* khi;      // [bh][npad][128] centroid hi parts        (pre-pass)
-  const __bf16* klo;      // [bh][npad][128] centroid lo parts
+  const __bf16* kcen;     // [bh][npad][128] kbar_j rounded to bf16    (pre-pass)
   const __bf16* vbar;     // [bh][npad][128] vsum_j / B_j
   const float* bias;      // [npad] log2 B_j, -inf past N
   const __bf16* hpack;    // [bh][2][8 ks][4 dt][64 lanes][8] hsum^T hi / lo in A-operand order
@@ -87,7 +86,7 @@ __device__ inline void split_bf16(float x, unsigned int& hi, unsigned int& lo) {
 // ---------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void attn_prep_kernel(
     const float* __restrict__ kbar, const float* __restrict__ vsum, const float* __restrict__ hsum,
-    __bf16* __restrict__ khi, __bf16* __restrict__ klo, __bf16* __restrict__ vbar,
+    __bf16* __restrict__ kcen, __bf16* __restrict__ vbar,
     float* __restrict__ bias, __bf16* __restrict__ hpack, int L, int B, int N, int npad) {
   const int tid = threadIdx.x;
   const size_t bh = blockIdx.y;
@@ -96,8 +95,7 @@ __global__ __launch_bounds__(256) void attn_prep_kernel(
   if (g < npad / kTile) {
     const float* kb = kbar + bh * (size_t)N * D;
     const float* vs = vsum + bh * (size_t)N * D;
-    unsigned char* oh = reinterpret_cast<unsigned char*>(khi + bh * (size_t)npad * D);
-    unsigned char* ol = reinterpret_cast<unsigned char*>(klo + bh * (size_t)npad * D);
+    unsigned char* ok = reinterpret_cast<unsigned char*>(kcen + bh * (size_t)npad * D);
     unsigned char* ov = reinterpret_cast<unsigned char*>(vbar + bh * (size_t)npad * D);
 #pragma unroll
     for (int it = 0; it < 8; ++it) {
@@ -111,17 +109,10 @@ __global__ __launch_bounds__(256) void attn_prep_kernel(
         vv = *reinterpret_cast<const float4*>(vs + (size_t)j * D + c4);
         vv.x *= inv; vv.y *= inv; vv.z *= inv; vv.w *= inv;
       }
-      unsigned int h0, l0, h1, l1, h2, l2, h3, l3;
-      split_bf16(kv.x, h0, l0);
-      split_bf16(kv.y, h1, l1);
-      split_bf16(kv.z, h2, l2);
-      split_bf16(kv.w, h3, l3);
-      const u32x2 hi = {h0 | (h1 << 16), h2 | (h3 << 16)};
-      const u32x2 lo = {l0 | (l1 << 16), l2 | (l3 << 16)};
+      const u32x2 kc = {pack_bf16(kv.x, kv.y), pack_bf16(kv.z, kv.w)};
       const u32x2 vb = {pack_bf16(vv.x, vv.y), pack_bf16(vv.z, vv.w)};
       const size_t o = (size_t)j * ROWB + c4 * 2;
-      *reinterpret_cast<u32x2*>(oh + o) = hi;
-      *reinterpret_cast<u32x2*>(ol + o) = lo;
+      *reinterpret_cast<u32x2*>(ok + o) = kc;
       *reinterpret_cast<u32x2*>(ov + o) = vb;
     }
     if (bh == 0 && tid < kTile) {
@@ -215,11 +206,11 @@ __device__ inline LDS_PTR(const unsigned char) xor_ptr(LDS_PTR(const unsigned ch
 __device__ inline void wait_async_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
 // ---- the three stages of one 64-key tile ------------------------------------------------
-// LDS offsets (KOFF, KOFF2, VOFF) are compile-time and relative to the staging origin the
+// LDS offsets (KOFF, VOFF) are compile-time and relative to the staging origin the
 // LaneCtx pointers refer to.
 
-// S^T = K_tile Q^T (TAIL: hi and lo centroid parts accumulate into the same S^T).
-template <bool TAIL, int KOFF, int KOFF2>
+// S^T = K_tile Q^T.
+template <int KOFF>
 __device__ inline void qk_tile(f32x16& s0, f32x16& s1, const bf16x8 (&qreg)[8], const LaneCtx& lc) {
   s0 = (f32x16){0};
   s1 = (f32x16){0};
@@ -230,16 +221,6 @@ __device__ inline void qk_tile(f32x16& s0, f32x16& s1, const bf16x8 (&qreg)[8], 
     const bf16x8 a1 = *reinterpret_cast<LDS_PTR(const bf16x8)>(kp + KOFF + 32 * ROWB);
     s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qreg[ks], s0, 0, 0, 0);
     s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qreg[ks], s1, 0, 0, 0);
-  }
-  if (TAIL) {
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      LDS_PTR(const unsigned char) kp = xor_ptr(lc.kbase, ks << 5);
-      const bf16x8 a0 = *reinterpret_cast<LDS_PTR(const bf16x8)>(kp + KOFF2);
-      const bf16x8 a1 = *reinterpret_cast<LDS_PTR(const bf16x8)>(kp + KOFF2 + 32 * ROWB);
-      s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qreg[ks], s0, 0, 0, 0);
-      s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qreg[ks], s1, 0, 0, 0);
-    }
   }
 }
 
@@ -345,19 +326,19 @@ __device__ inline void pv_tile(State& st, const bf16x8 (&pb)[4], const LaneCtx& 
 }
 
 // One staged tile, start to finish (ragged tile, centroid tiles).
-template <bool TAIL, bool RAGGED, int KOFF, int KOFF2, int VOFF>
+template <bool TAIL, bool RAGGED, int KOFF, int VOFF>
 __device__ inline void absorb_tile(State& st, const bf16x8 (&qreg)[8], const LaneCtx& lc,
                                    LDS_PTR(const float) bias, int nvalid, float c) {
   f32x16 s0, s1;
   bf16x8 pb[4];
-  qk_tile<TAIL, KOFF, KOFF2>(s0, s1, qreg, lc);
+  qk_tile<KOFF>(s0, s1, qreg, lc);
   const float m_safe = softmax_max<TAIL>(st, s0, s1, lc, bias, c);
   softmax_exp<TAIL, RAGGED>(st, s0, s1, m_safe, pb, lc, nvalid, c);
   pv_tile<VOFF>(st, pb, lc);
 }
 
 // LDS map of the staging area (byte offsets): K stages | V stages; Phase 2 reuses it as
-// khi | klo | vbar.
+// centroid keys (K stage 0) and centroid values (V stage 0).
 constexpr int KST0 = 0, KST1 = TILEB, VST0 = 2 * TILEB, VST1 = 3 * TILEB;
 
 template <bool DENSE>
@@ -514,7 +495,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
     __syncthreads();
     if (have1) issue_k(t1, KST1);
     issue_v(t0, VST0);
-    if ((in0 >> qb) & 1) qk_tile<false, KST0, 0>(sc0, sc1, qreg, lc);
+    if ((in0 >> qb) & 1) qk_tile<KST0>(sc0, sc1, qreg, lc);
   }
   auto trip = [&](auto parity_tag) {
     constexpr int P = decltype(parity_tag)::value;       // parity of the current tile
@@ -532,7 +513,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
       bf16x8 pb[4];
       const float m_safe = softmax_max<false>(st, sc0, sc1, lc, nullptr, c);
       // straight-line from here: S^T(t+1) on the matrix cores, exp / sum / pack on the VALU
-      qk_tile<false, K_NEXT, 0>(sn0, sn1, qreg, lc);
+      qk_tile<K_NEXT>(sn0, sn1, qreg, lc);
       softmax_exp<false, false>(st, sc0, sc1, m_safe, pb, lc, kTile, c);
       pv_tile<V_CUR>(st, pb, lc);
       sc0 = sn0;
@@ -543,7 +524,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
       softmax_exp<false, false>(st, sc0, sc1, m_safe, pb, lc, kTile, c);
       pv_tile<V_CUR>(st, pb, lc);
     } else if (do_next) {
-      qk_tile<false, K_NEXT, 0>(sc0, sc1, qreg, lc);
+      qk_tile<K_NEXT>(sc0, sc1, qreg, lc);
     }
     t0 = t1; in0 = in1; have0 = have1;
     t1 = t2; in1 = in2; have1 = have2;
@@ -567,22 +548,20 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
       wait_async_loads();
       __syncthreads();
       if ((inm >> qb) & 1)
-        absorb_tile<false, true, KST0, 0, VST0>(st, qreg, lc, nullptr, L - tile * kTile, c);
+        absorb_tile<false, true, KST0, VST0>(st, qreg, lc, nullptr, L - tile * kTile, c);
     }
   }
 
-  // ---- Phase 2: centroid tiles (hi, lo, values) ----
-  const bool approx = !DENSE && p.k_top < N && p.khi != nullptr;   // khi == nullptr: keep-or-drop
+  // ---- Phase 2: centroid tiles (keys, values) ----
+  const bool approx = !DENSE && p.k_top < N && p.kcen != nullptr;   // kcen == nullptr: keep-or-drop
   if (approx) {
-    const unsigned char* khg = reinterpret_cast<const unsigned char*>(p.khi + bh * (size_t)p.npad * D);
-    const unsigned char* klg = reinterpret_cast<const unsigned char*>(p.klo + bh * (size_t)p.npad * D);
+    const unsigned char* kcg = reinterpret_cast<const unsigned char*>(p.kcen + bh * (size_t)p.npad * D);
     const unsigned char* vbg = reinterpret_cast<const unsigned char*>(p.vbar + bh * (size_t)p.npad * D);
     LDS_PTR(const float) my_bias = (LDS_PTR(const float)) & bias_s[qb][0];
     for (int g0 = 0; g0 < N; g0 += kTile) {
       __syncthreads();                         // previous tile fully consumed
-      load_tile_async<true>(lc, khg + (size_t)g0 * ROWB, kTile, lds_addr);
-      load_tile_async<true>(lc, klg + (size_t)g0 * ROWB, kTile, lds_addr + TILEB);
-      load_tile_async<false>(lc, vbg + (size_t)g0 * ROWB, kTile, lds_addr + 2 * TILEB);
+      load_tile_async<true>(lc, kcg + (size_t)g0 * ROWB, kTile, lds_addr + KST0);
+      load_tile_async<false>(lc, vbg + (size_t)g0 * ROWB, kTile, lds_addr + VST0);
       if (tid < 2 * kTile) {
         const int b = tid >> 6, j = g0 + (tid & 63);
         const bool masked =
@@ -591,7 +570,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
       }
       wait_async_loads();
       __syncthreads();
-      absorb_tile<true, false, 0, TILEB, 2 * TILEB>(st, qreg, lc, my_bias, kTile, c);
+      absorb_tile<true, false, KST0, VST0>(st, qreg, lc, my_bias, kTile, c);
     }
   }
 
@@ -641,7 +620,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
 size_t attention_workspace_bytes(const Dims& dm) {
   if (dm.dtype != PISA_BF16) return 0;
   const size_t npad = (size_t)((dm.N + kTile - 1) / kTile) * kTile;
-  return (size_t)dm.bh() * (3 * npad * D * 2 + 2 * D * D * 2) + npad * sizeof(float);
+  return (size_t)dm.bh() * (2 * npad * D * 2 + 2 * D * D * 2) + npad * sizeof(float);
 }
 
 hipError_t launch_attention_bf16(const Dims& dm, const AttnArgs& a, hipStream_t stream) {
@@ -667,20 +646,18 @@ hipError_t launch_attention_bf16(const Dims& dm, const AttnArgs& a, hipStream_t 
     return hipGetLastError();
   }
   if (a.k_top < dm.N && a.kbar) {
-    // carve the workspace: khi | klo | vbar | hpack | bias
+    // carve the workspace: kcen | vbar | hpack | bias
     unsigned char* ws = static_cast<unsigned char*>(a.workspace);
     const size_t tile_elems = (size_t)dm.bh() * p.npad * D;
-    __bf16* khi = reinterpret_cast<__bf16*>(ws);
-    __bf16* klo = khi + tile_elems;
-    __bf16* vbar = klo + tile_elems;
+    __bf16* kcen = reinterpret_cast<__bf16*>(ws);
+    __bf16* vbar = kcen + tile_elems;
     __bf16* hpack = vbar + tile_elems;
     float* bias = reinterpret_cast<float*>(hpack + (size_t)dm.bh() * 2 * D * D);
     hipLaunchKernelGGL(attn_prep_kernel, dim3(p.npad / kTile + 1, dm.bh()), dim3(256), 0, stream,
-                       a.kbar, a.vsum, a.hsum, khi, klo, vbar, bias, hpack, dm.L, dm.B, dm.N, p.npad);
+                       a.kbar, a.vsum, a.hsum, kcen, vbar, bias, hpack, dm.L, dm.B, dm.N, p.npad);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    p.khi = khi;
-    p.klo = klo;
+    p.kcen = kcen;
     p.vbar = vbar;
     p.hpack = hpack;
     p.bias = bias;
