@@ -304,6 +304,36 @@ __device__ inline void softmax_exp(State& st, const f32x16& s0, const f32x16& s1
   }
 }
 
+// Fast step for a full exact tile: probabilities against the running max AS IT STANDS (no
+// new maximum is taken, so no cross-lane exchange and no rescale), packed to bf16, with
+// their row-sum.  fp32 and bf16 share their exponent range, so a stale maximum costs no
+// accuracy until 2^(logit - max) nears overflow: the caller falls back to the exact step
+// (softmax_max, then this again) when some lane's sum is not below kStaleLimit.  Sums stay
+// below 2^60 between refreshes, so l and O (at most a few 10^5 keys of bounded values) stay
+// far from the fp32 limit.  A wave that has absorbed nothing yet (max = -inf) gets +inf
+// everywhere and therefore always falls back on its first tile; NaN falls back as well.
+constexpr float kStaleLimit = 0x1p60f;
+__device__ inline float softmax_exp_stale(const State& st, const f32x16& s0, const f32x16& s1,
+                                         bf16x8 (&pb)[4], float c) {
+  const float nm = -st.m;
+  float pa = 0.f, pc = 0.f;
+#pragma unroll
+  for (int step = 0; step < 4; ++step) {            // keys 16 step .. 16 step + 15
+    u32x4 pw;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int r = (8 * step + 2 * i) & 15;        // registers r, r + 1 of s0 (steps 0, 1) or s1
+      const float x0 = __builtin_amdgcn_exp2f(fmaf(step < 2 ? s0[r] : s1[r], c, nm));
+      const float x1 = __builtin_amdgcn_exp2f(fmaf(step < 2 ? s0[r + 1] : s1[r + 1], c, nm));
+      pw[i] = pack_bf16(x0, x1);
+      if (i & 1) pc += x0 + x1;
+      else pa += x0 + x1;
+    }
+    pb[step] = __builtin_bit_cast(bf16x8, pw);
+  }
+  return pa + pc;
+}
+
 // O^T += V^T P^T: four contraction steps of 16 keys.  Transposed LDS read: lane j of a
 // 16-lane group points at 4 channels of key (j >> 2) and receives channel (group base + j)
 // of the group's four keys.
@@ -511,17 +541,25 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
     if (do_cur && do_next) {
       f32x16 sn0, sn1;
       bf16x8 pb[4];
-      const float m_safe = softmax_max<false>(st, sc0, sc1, lc, nullptr, c);
-      // straight-line from here: S^T(t+1) on the matrix cores, exp / sum / pack on the VALU
+      // straight-line: S^T(t+1) on the matrix cores, exp / sum / pack of tile t on the VALU
       qk_tile<K_NEXT>(sn0, sn1, qreg, lc);
-      softmax_exp<false, false>(st, sc0, sc1, m_safe, pb, lc, kTile, c);
+      float psum = softmax_exp_stale(st, sc0, sc1, pb, c);
+      if (__any(!(psum < kStaleLimit))) {          // first tile of this wave, or a maximum that ran away
+        softmax_max<false>(st, sc0, sc1, lc, nullptr, c);
+        psum = softmax_exp_stale(st, sc0, sc1, pb, c);
+      }
+      st.l += psum;
       pv_tile<V_CUR>(st, pb, lc);
       sc0 = sn0;
       sc1 = sn1;
     } else if (do_cur) {
       bf16x8 pb[4];
-      const float m_safe = softmax_max<false>(st, sc0, sc1, lc, nullptr, c);
-      softmax_exp<false, false>(st, sc0, sc1, m_safe, pb, lc, kTile, c);
+      float psum = softmax_exp_stale(st, sc0, sc1, pb, c);
+      if (__any(!(psum < kStaleLimit))) {
+        softmax_max<false>(st, sc0, sc1, lc, nullptr, c);
+        psum = softmax_exp_stale(st, sc0, sc1, pb, c);
+      }
+      st.l += psum;
       pv_tile<V_CUR>(st, pb, lc);
     } else if (do_next) {
       qk_tile<K_NEXT>(sc0, sc1, qreg, lc);

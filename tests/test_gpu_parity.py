@@ -229,6 +229,46 @@ def test_covariance_aware_selection(lib, dtype, d, B, L):
         assert rel <= TOL[q.dtype] and cos >= COS_MIN
 
 
+@pytest.mark.parametrize("direction", ["rising", "falling", "spike"])
+def test_runaway_maximum(lib, direction):
+    """Logits that climb (or drop) by hundreds along the key axis: the bf16 kernel's running
+    maximum, which is only refreshed when a tile sum nears overflow, must keep up in both the
+    dense and the PISA walk; a single huge key in the middle must not poison what follows."""
+    L, H, d, B = 2304, 2, 128, 64
+    w = WORKLOADS["flux"].with_(name=f"runaway-{direction}", heads=H, seq_len=L, grid=None, sparsity=0.5)
+    q, k, v = make_qkv(w, device="cpu")
+    u = torch.zeros(d)
+    u[:8] = 1.0
+    pos = torch.arange(L, dtype=torch.float32) / L
+    ramp = {"rising": pos - 0.5, "falling": 0.5 - pos, "spike": torch.zeros(L)}[direction]
+    if direction == "spike":
+        ramp[L // 2 + 5] = 1.0
+    # q gets a constant component along u, k a component that grows with position: the logit
+    # s q.k moves by about +-600 (natural units) over the sequence, ~17 per 64-key tile.
+    q = (q.float() * 0.25 + 24.0 * u).to(torch.bfloat16)
+    k = (k.float() * 0.25 + (35.0 * ramp)[:, None] * u).to(torch.bfloat16)
+    qd, kd, vd = q.to(DEV), k.to(DEV), v.to(DEV)
+    scale = lib.resolved_scale(d)
+    dense, dense_lse = lib.dense_attention(qd, kd, vd, B, want_lse=True)
+    res = lib.pisa_forward(qd, kd, vd, B, w.sparsity, want_lse=True)
+    torch.cuda.synchronize()
+    assert torch.isfinite(dense.float()).all() and torch.isfinite(res["out"].float()).all()
+    blocks = [0, 1, 17, 35]
+    rows = rows_of_blocks(blocks, B, L)
+    for h in range(H):
+        Q, K, V = head_np(q, 0, h), head_np(k, 0, h), head_np(v, 0, h)
+        st = po.block_stats(Q, K, V, B)
+        dref, dlse = po.attention_head(Q, K, V, B, None, scale, "dense", blocks=blocks)
+        rel, cos = row_errors(dense[0, h].float().cpu().numpy()[rows], dref)
+        assert rel <= TOL[q.dtype] and cos >= COS_MIN, (direction, h, "dense", rel, cos)
+        assert np.abs(dense_lse[0, h].cpu().numpy()[rows] - dlse).max() <= 2e-2 * max(1.0, np.abs(dlse).max() / 50)
+        ref, rlse = po.attention_head(Q, K, V, B, res["idx"][0, h].cpu().numpy(), scale, "hybrid",
+                                      blocks=blocks, stats=st)
+        rel, cos = row_errors(res["out"][0, h].float().cpu().numpy()[rows], ref)
+        assert rel <= TOL[q.dtype] and cos >= COS_MIN, (direction, h, "pisa", rel, cos)
+        print(f"[parity] runaway {direction} head {h}: pisa {rel:.2e} lse range {dlse.min():.1f}..{dlse.max():.1f}")
+
+
 def test_flux_config_full(lib):
     """FLUX.1-dev-shaped config (24 heads, N=4608, bf16, r=0.85) compared in full."""
     run_full_case(lib, WORKLOADS["flux"])
