@@ -191,6 +191,18 @@ __device__ inline void load_tile_async(const LaneCtx& lc, const unsigned char* t
   }
 }
 
+// Load i (of four) of this wave's share of a FULL tile: the same instruction as in
+// load_tile_async, one at a time.
+template <bool KFMT>
+__device__ inline void load_tile_part(const LaneCtx& lc, const unsigned char* tile_base, unsigned lds_stage, int i) {
+  const unsigned voff = KFMT ? lc.dma_k : lc.dma_v;
+  const unsigned m0_0 = __builtin_amdgcn_readfirstlane(lds_stage + lc.wave * 1024);
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(m0_0 + i * 4096), "v"(voff), "s"(tile_base + i * 4096)
+               : "memory", "m0");
+}
+
 // V-format swizzle: the 32-byte chunk index of row r is XORed with this 3-bit value.  The
 // four consecutive rows a 16-lane group reads together get 0,2,4,6 (or 1,3,5,7), so the two
 // groups of a half-wave (chunk indices differing in bit 0) hit disjoint banks: measured
@@ -221,6 +233,34 @@ __device__ inline void qk_tile(f32x16& s0, f32x16& s1, const bf16x8 (&qreg)[8], 
     const bf16x8 a1 = *reinterpret_cast<LDS_PTR(const bf16x8)>(kp + KOFF + 32 * ROWB);
     s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qreg[ks], s0, 0, 0, 0);
     s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qreg[ks], s1, 0, 0, 0);
+  }
+}
+
+// qk_tile with the eight LDS-DMA loads of the next K / V tiles issued between its MFMAs, so
+// that the issue cost of a load hides under a running MFMA.  K operands are read one step
+// ahead of their use (the loads order LDS reads around them).
+template <int KOFF>
+__device__ inline void qk_tile_dma(f32x16& s0, f32x16& s1, const bf16x8 (&qreg)[8], const LaneCtx& lc,
+                                   const unsigned char* kt, unsigned k_stage, const unsigned char* vt,
+                                   unsigned v_stage) {
+  s0 = (f32x16){0};
+  s1 = (f32x16){0};
+  bf16x8 a0 = *reinterpret_cast<LDS_PTR(const bf16x8)>(lc.kbase + KOFF);
+  bf16x8 a1 = *reinterpret_cast<LDS_PTR(const bf16x8)>(lc.kbase + KOFF + 32 * ROWB);
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    bf16x8 n0 = a0, n1 = a1;
+    if (ks < 7) {
+      LDS_PTR(const unsigned char) kp = xor_ptr(lc.kbase, (ks + 1) << 5);
+      n0 = *reinterpret_cast<LDS_PTR(const bf16x8)>(kp + KOFF);
+      n1 = *reinterpret_cast<LDS_PTR(const bf16x8)>(kp + KOFF + 32 * ROWB);
+    }
+    s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qreg[ks], s0, 0, 0, 0);
+    s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qreg[ks], s1, 0, 0, 0);
+    if (ks < 4) load_tile_part<true>(lc, kt, k_stage, ks);
+    else load_tile_part<false>(lc, vt, v_stage, ks - 4);
+    a0 = n0;
+    a1 = n1;
   }
 }
 
@@ -513,7 +553,8 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
   // wave issues S^T(t+1) on the matrix cores while the vector ALUs work through the softmax
   // of tile t (the two are independent), then O^T += V(t)^T P(t)^T.  One barrier per trip:
   // after it K(t+1) and V(t) have landed and K stage t&1 / V stage (t+1)&1 are free, so the
-  // loads of K(t+2) and V(t+1) go out right away.
+  // loads of K(t+2) and V(t+1) go out during the trip, between the MFMAs of S^T(t+1) (a wave
+  // of a block that skips the tile issues its share up front).
   int t0 = 0, in0 = 0, t1 = 0, in1 = 0, t2 = 0, in2 = 0;
   bool have0 = next_tile(t0, in0);
   bool have1 = false, have2 = false;
@@ -534,15 +575,16 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
     have2 = have1 && next_tile(t2, in2);
     wait_async_loads();
     __syncthreads();
-    if (have2) issue_k(t2, K_FREE);
-    if (have1) issue_v(t1, V_FREE);
     const bool do_cur = (in0 >> qb) & 1;
     const bool do_next = have1 && ((in1 >> qb) & 1);
+    // Past the end of the walk the loads repeat tile t0 into the free stages (harmless).
+    const int tk = have2 ? t2 : t0, tv = have1 ? t1 : t0;
     if (do_cur && do_next) {
       f32x16 sn0, sn1;
       bf16x8 pb[4];
       // straight-line: S^T(t+1) on the matrix cores, exp / sum / pack of tile t on the VALU
-      qk_tile<K_NEXT>(sn0, sn1, qreg, lc);
+      qk_tile_dma<K_NEXT>(sn0, sn1, qreg, lc, kg + (size_t)tk * TILEB, lds_addr + K_FREE,
+                          vg + (size_t)tv * TILEB, lds_addr + V_FREE);
       float psum = softmax_exp_stale(st, sc0, sc1, pb, c);
       if (__any(!(psum < kStaleLimit))) {          // first tile of this wave, or a maximum that ran away
         softmax_max<false>(st, sc0, sc1, lc, nullptr, c);
@@ -553,6 +595,8 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
       sc0 = sn0;
       sc1 = sn1;
     } else if (do_cur) {
+      issue_k(tk, K_FREE);
+      issue_v(tv, V_FREE);
       bf16x8 pb[4];
       float psum = softmax_exp_stale(st, sc0, sc1, pb, c);
       if (__any(!(psum < kStaleLimit))) {
@@ -561,8 +605,10 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
       }
       st.l += psum;
       pv_tile<V_CUR>(st, pb, lc);
-    } else if (do_next) {
-      qk_tile<K_NEXT>(sc0, sc1, qreg, lc);
+    } else {
+      issue_k(tk, K_FREE);
+      issue_v(tv, V_FREE);
+      if (do_next) qk_tile<K_NEXT>(sc0, sc1, qreg, lc);
     }
     t0 = t1; in0 = in1; have0 = have1;
     t1 = t2; in1 = in2; have1 = have2;
@@ -572,6 +618,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
     if (!have0) break;
     trip(std::integral_constant<int, 1>{});
   }
+  wait_async_loads();                      // the last trips' repeated loads
 
   // ---- ragged last tile (L not a multiple of 64), if this workgroup attends it ----
   if (L % kTile != 0) {
