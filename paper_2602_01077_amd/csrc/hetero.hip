@@ -2,13 +2,15 @@
 // bias log(M_j + eps) of the covariance-aware selection score (Methodology,
 // "Covariance-Aware Block Selection"; H_j from "Global First-Order Correction").
 //
-// Everything here is fp64 on the vector ALUs: the bias is added to fp64 pooled logits and
-// has to keep their accuracy.  Two passes over K and V, no per-block matrices in memory:
-//   (1) hsum64_kernel   one workgroup per chunk of blocks accumulates sum_j H_j; the partial
-//                       sums are added in chunk order and divided by N (hbar64_kernel);
-//   (2) hetero_kernel   one workgroup per block rebuilds H_j, subtracts Hbar and takes the
-//                       Frobenius norm, or the spectral norm by power iteration on D^T D.
-// A thread owns an R x R patch (R = d/16) of the d x d matrix.
+// Everything here is fp64: the bias is added to fp64 pooled logits and has to keep their
+// accuracy.  Two passes over K and V, no per-block matrices in memory:
+//   (1) hsum64_kernel   one workgroup per chunk of blocks accumulates sum_j H_j on the fp64
+//                       matrix cores; the partial sums are added in chunk order and divided
+//                       by N (hbar64_kernel);
+//   (2) frob_kernel     one workgroup per block rebuilds H_j the same way, subtracts Hbar and
+//                       takes the Frobenius norm; or
+//       hetero_kernel   (spectral norm) rebuilds H_j on the vector ALUs, a thread owning an
+//                       R x R patch (R = d/16), and runs a power iteration on D^T D.
 #include <hip/hip_bf16.h>
 
 #include "common.h"
@@ -51,32 +53,165 @@ __device__ inline void add_block_H(double (&h)[D / 16][D / 16], const T* kh, con
   }
 }
 
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+
+// Matrix-core version of add_block_H.  The d x d matrix is split over the four waves in
+// quadrants; wave w holds TR x TR tiles of 16 x 16 (TR = d/32) as v_mfma_f64_16x16x4_f64
+// accumulators: acc[a][b][e] <-> H[rb + 16a + 4e + l/16][cb + 16b + l%16], rb = (d/2)(w/2),
+// cb = (d/2)(w%2).  Per step of four tokens a lane supplies A[l%16][l/16] = centred key
+// channel rb + 16a + l%16 of token l/16 and B[l/16][l%16] = value channel cb + 16b + l%16.
+// Rows of the LDS staging are padded by 16 elements so the four token rows of a step fall
+// on different banks; tokens are staged 32 at a time with 16-byte loads.
+constexpr int kSub = 32;   // tokens staged at a time (two workgroups per CU fit their LDS)
+template <int D> struct HStage {
+  static constexpr int P = D + 16;
+  double kc[kSub][P];
+  float vs[kSub][P];
+};
+
+// 16 bytes of consecutive channels of one row, widened to fp64.
+template <typename T> struct Vec16;
+template <> struct Vec16<float> {
+  static constexpr int N = 4;
+  static __device__ inline void load(const float* p, double (&out)[4]) {
+    const float4 x = *reinterpret_cast<const float4*>(p);
+    out[0] = x.x; out[1] = x.y; out[2] = x.z; out[3] = x.w;
+  }
+};
+template <> struct Vec16<__hip_bfloat16> {
+  static constexpr int N = 8;
+  static __device__ inline void load(const __hip_bfloat16* p, double (&out)[8]) {
+    const uint4 x = *reinterpret_cast<const uint4*>(p);
+    const unsigned w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      out[2 * i] = (double)__uint_as_float(w[i] << 16);
+      out[2 * i + 1] = (double)__uint_as_float(w[i] & 0xffff0000u);
+    }
+  }
+};
+
 template <typename T, int D>
-__global__ __launch_bounds__(256) void hsum64_kernel(const T* __restrict__ k, const T* __restrict__ v,
+__device__ inline void add_block_H_mfma(f64x4 (&acc)[D / 32][D / 32], const T* kh, const T* vh,
+                                        const double* kmean, int row0, int rows, HStage<D>& sh) {
+  constexpr int TR = D / 32;
+  constexpr int EPV = Vec16<T>::N;           // channels per 16-byte load
+  constexpr int CPR = D / EPV;               // loads per row; divides 256, so a thread keeps its channels
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int i16 = lane & 15, kk = lane >> 4;
+  const int rb = (D / 2) * (wave >> 1), cb = (D / 2) * (wave & 1);
+  const int c0 = (tid % CPR) * EPV;
+  double mean[EPV];
+#pragma unroll
+  for (int i = 0; i < EPV; ++i) mean[i] = kmean[c0 + i];
+  for (int sub = 0; sub < rows; sub += kSub) {
+    const int nv = min(kSub, rows - sub);
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < kSub * CPR / 256; ++it) {
+      const int n = (it * 256 + tid) / CPR;
+      double kv[EPV], vv[EPV];
+#pragma unroll
+      for (int i = 0; i < EPV; ++i) kv[i] = vv[i] = 0.0;
+      if (n < nv) {                          // rows past the block contribute zeros
+        const size_t off = (size_t)(row0 + sub + n) * D + c0;
+        Vec16<T>::load(kh + off, kv);
+        Vec16<T>::load(vh + off, vv);
+#pragma unroll
+        for (int i = 0; i < EPV; ++i) kv[i] -= mean[i];
+      }
+#pragma unroll
+      for (int i = 0; i < EPV; ++i) {
+        sh.kc[n][c0 + i] = kv[i];
+        sh.vs[n][c0 + i] = (float)vv[i];
+      }
+    }
+    __syncthreads();
+    const int steps = (nv + 3) / 4;
+    for (int s4 = 0; s4 < steps; ++s4) {
+      const int n = 4 * s4 + kk;
+      double af[TR], bf[TR];
+#pragma unroll
+      for (int a = 0; a < TR; ++a) af[a] = sh.kc[n][rb + 16 * a + i16];
+#pragma unroll
+      for (int b = 0; b < TR; ++b) bf[b] = (double)sh.vs[n][cb + 16 * b + i16];
+#pragma unroll
+      for (int a = 0; a < TR; ++a)
+#pragma unroll
+        for (int b = 0; b < TR; ++b)
+          acc[a][b] = __builtin_amdgcn_mfma_f64_16x16x4f64(af[a], bf[b], acc[a][b], 0, 0, 0);
+    }
+  }
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(256, 2) void hsum64_kernel(const T* __restrict__ k, const T* __restrict__ v,
                                                      const double* __restrict__ kbar64,
                                                      double* __restrict__ partial, int L, int B, int N,
                                                      int chunk_blocks, int n_chunks) {
-  constexpr int R = D / 16;
-  __shared__ double kc[kTile][D];
-  __shared__ float vs[kTile][D];
-  const int tid = threadIdx.x, ta = tid / 16, tb = tid % 16;
+  constexpr int TR = D / 32;
+  __shared__ HStage<D> sh;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int chunk = blockIdx.x;
   const size_t bh = blockIdx.y;
   const T* kh = k + bh * (size_t)L * D;
   const T* vh = v + bh * (size_t)L * D;
-  double h[R][R];
+  f64x4 acc[TR][TR];
 #pragma unroll
-  for (int a = 0; a < R; ++a)
+  for (int a = 0; a < TR; ++a)
 #pragma unroll
-    for (int b = 0; b < R; ++b) h[a][b] = 0.0;
+    for (int b = 0; b < TR; ++b) acc[a][b] = f64x4{0.0, 0.0, 0.0, 0.0};
   const int j_end = min(N, (chunk + 1) * chunk_blocks);
   for (int j = chunk * chunk_blocks; j < j_end; ++j)
-    add_block_H<T, D>(h, kh, vh, kbar64 + (bh * N + j) * D, j * B, min(B, L - j * B), kc, vs);
+    add_block_H_mfma<T, D>(acc, kh, vh, kbar64 + (bh * N + j) * D, j * B, min(B, L - j * B), sh);
   double* ph = partial + (bh * n_chunks + chunk) * (size_t)D * D;
+  const int rb = (D / 2) * (wave >> 1), cb = (D / 2) * (wave & 1);
 #pragma unroll
-  for (int a = 0; a < R; ++a)
+  for (int a = 0; a < TR; ++a)
 #pragma unroll
-    for (int b = 0; b < R; ++b) ph[(size_t)(ta * R + a) * D + tb * R + b] = h[a][b];
+    for (int b = 0; b < TR; ++b)
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        ph[(size_t)(rb + 16 * a + 4 * e + (lane >> 4)) * D + cb + 16 * b + (lane & 15)] = acc[a][b][e];
+}
+
+// M_j = || H_j - Hbar ||_F for one block per workgroup.
+template <typename T, int D>
+__global__ __launch_bounds__(256, 2) void frob_kernel(const T* __restrict__ k, const T* __restrict__ v,
+                                                   const double* __restrict__ kbar64,
+                                                   const double* __restrict__ hbar64,
+                                                   double* __restrict__ log_m, int L, int B, int N, double eps) {
+  constexpr int TR = D / 32;
+  __shared__ HStage<D> sh;
+  __shared__ double red[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int j = blockIdx.x;
+  const size_t bh = blockIdx.y;
+  f64x4 acc[TR][TR];
+#pragma unroll
+  for (int a = 0; a < TR; ++a)
+#pragma unroll
+    for (int b = 0; b < TR; ++b) acc[a][b] = f64x4{0.0, 0.0, 0.0, 0.0};
+  add_block_H_mfma<T, D>(acc, k + bh * (size_t)L * D, v + bh * (size_t)L * D, kbar64 + (bh * N + j) * D,
+                         j * B, min(B, L - j * B), sh);
+  const double* hb = hbar64 + bh * (size_t)D * D;
+  const int rb = (D / 2) * (wave >> 1), cb = (D / 2) * (wave & 1);
+  double ss = 0.0;
+#pragma unroll
+  for (int a = 0; a < TR; ++a)
+#pragma unroll
+    for (int b = 0; b < TR; ++b)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const double dv =
+            acc[a][b][e] - hb[(size_t)(rb + 16 * a + 4 * e + (lane >> 4)) * D + cb + 16 * b + (lane & 15)];
+        ss = fma(dv, dv, ss);
+      }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off);
+  if (lane == 0) red[wave] = ss;
+  __syncthreads();
+  if (tid == 0) log_m[bh * N + j] = log(sqrt((red[0] + red[1]) + (red[2] + red[3])) + eps);
 }
 
 // hbar64[bh][e] = (sum over chunks, in chunk order, of partial[bh][chunk][e]) / N
@@ -219,8 +354,12 @@ hipError_t launch_block_heterogeneity(const Dims& dm, const void* k, const void*
     hipLaunchKernelGGL((hsum64_kernel<T, DD>), g1, dim3(256), 0, stream, (const T*)k, (const T*)v,      \
                        kbar64, partial, dm.L, dm.B, dm.N, plan.chunk_blocks, plan.n_chunks);            \
     hipLaunchKernelGGL(hbar64_kernel, g2, dim3(256), 0, stream, partial, hbar, plan.n_chunks, dd, dm.N); \
-    hipLaunchKernelGGL((hetero_kernel<T, DD>), g3, dim3(256), 0, stream, (const T*)k, (const T*)v,      \
-                       kbar64, hbar, log_m, dm.L, dm.B, dm.N, spectral, n_iter, eps);                   \
+    if (spectral)                                                                                       \
+      hipLaunchKernelGGL((hetero_kernel<T, DD>), g3, dim3(256), 0, stream, (const T*)k, (const T*)v,    \
+                         kbar64, hbar, log_m, dm.L, dm.B, dm.N, spectral, n_iter, eps);                 \
+    else                                                                                                \
+      hipLaunchKernelGGL((frob_kernel<T, DD>), g3, dim3(256), 0, stream, (const T*)k, (const T*)v,      \
+                         kbar64, hbar, log_m, dm.L, dm.B, dm.N, eps);                                   \
   } while (0)
   if (dm.dtype == PISA_BF16)
     PISA_HET(__hip_bfloat16, 128);
