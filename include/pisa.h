@@ -15,7 +15,8 @@
  * Conventions
  *   - All tensor pointers are DEVICE pointers owned by the caller; the library never
  *     allocates, frees or synchronises.  Work is enqueued on `stream`
- *     (a hipStream_t passed as void*; NULL = the default stream).
+ *     (a hipStream_t passed as void*; NULL = the default stream).  Every tensor and
+ *     workspace pointer must be 16-byte aligned (PISA_INVALID_ARG otherwise).
  *   - Layout: Q, K, V, O are dense [batch, heads, seq_len, head_dim], head_dim contiguous.
  *     Blocks are consecutive runs of `block` tokens; N = ceil(seq_len / block); the last
  *     block may be ragged (B_j < block rows) -- statistics run over its valid rows.

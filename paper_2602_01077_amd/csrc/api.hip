@@ -6,6 +6,8 @@
 #include <cstdarg>
 #include <cstdio>
 
+#include <initializer_list>
+
 #include "common.h"
 
 namespace pisa {
@@ -74,6 +76,15 @@ static size_t stats_workspace_bytes(const Dims& dm) {
 
 using namespace pisa;
 
+// The kernels move 16 bytes per lane: every tensor pointer has to sit on a 16-byte boundary.
+static bool misaligned(std::initializer_list<const void*> ptrs) {
+  for (const void* p : ptrs)
+    if (reinterpret_cast<uintptr_t>(p) & 15u) return true;
+  return false;
+}
+#define PISA_CHECK_ALIGN(...)                                                                   \
+  if (misaligned({__VA_ARGS__})) return fail(PISA_INVALID_ARG, "tensor and workspace pointers must be 16-byte aligned")
+
 extern "C" {
 
 int32_t pisa_num_blocks(int32_t seq_len, int32_t block) {
@@ -107,6 +118,7 @@ int32_t pisa_block_stats(const pisa_shape* shape, const void* q, const void* k, 
   if (!q || !k || !v) return fail(PISA_INVALID_ARG, "q, k, v must not be NULL");
   if (!qbar || !kbar || !vsum || !hsum || !qbar64 || !kbar64)
     return fail(PISA_INVALID_ARG, "qbar, kbar, vsum, hsum, qbar64, kbar64 must not be NULL");
+  PISA_CHECK_ALIGN(q, k, v, qbar, kbar, vsum, hsum, qbar64, kbar64, workspace);
   size_t need = stats_workspace_bytes(dm);
   if (!workspace) return fail(PISA_INVALID_ARG, "workspace is NULL (need %zu bytes)", need);
   if (workspace_bytes < need)
@@ -127,6 +139,7 @@ int32_t pisa_block_heterogeneity(const pisa_shape* shape, const void* k, const v
   if (norm_kind != PISA_NORM_SPECTRAL && norm_kind != PISA_NORM_FROBENIUS)
     return fail(PISA_INVALID_ARG, "norm_kind must be PISA_NORM_SPECTRAL (0) or PISA_NORM_FROBENIUS (1)");
   if (!(eps >= 0.0)) return fail(PISA_INVALID_ARG, "eps must be >= 0");
+  PISA_CHECK_ALIGN(k, v, kbar64, log_m, workspace);
   size_t need = hetero_workspace_bytes(dm);
   if (!workspace) return fail(PISA_INVALID_ARG, "workspace is NULL (need %zu bytes)", need);
   if (workspace_bytes < need)
@@ -148,6 +161,7 @@ int32_t pisa_select(const pisa_shape* shape, const double* qbar64, const double*
   if (k_top < 0 || k_top > dm.N)
     return fail(PISA_INVALID_ARG, "k_top = %d outside [0, N = %d]", k_top, dm.N);
   if (k_top > 0 && !idx) return fail(PISA_INVALID_ARG, "idx is NULL but k_top > 0");
+  PISA_CHECK_ALIGN(qbar64, kbar64, col_bias, idx, kth_gap, workspace);
   if (dm.N > kMaxBlocks)
     return fail(PISA_UNSUPPORTED, "at most %d blocks are supported (N = %d)", kMaxBlocks, dm.N);
   size_t need = select_workspace_bytes(dm);
@@ -183,6 +197,7 @@ int32_t pisa_attention(const pisa_shape* shape, const void* q, const void* k, co
     return fail(PISA_INVALID_ARG, "kbar and vsum must both be given or both be NULL");
   if (!kbar && k_top == 0)
     return fail(PISA_INVALID_ARG, "keep-or-drop mode (kbar == vsum == NULL) needs k_top >= 1");
+  PISA_CHECK_ALIGN(q, k, v, kbar, vsum, hsum, idx, out, lse, workspace);
   if (dm.N > kMaxBlocks)
     return fail(PISA_UNSUPPORTED, "at most %d blocks are supported (N = %d)", kMaxBlocks, dm.N);
   if (k_top < dm.N && kbar) {
@@ -201,6 +216,7 @@ int32_t dense_attention(const pisa_shape* shape, const void* q, const void* k, c
   int32_t rc = resolve(shape, &dm);
   if (rc != PISA_OK) return rc;
   if (!q || !k || !v || !out) return fail(PISA_INVALID_ARG, "q, k, v, out must not be NULL");
+  PISA_CHECK_ALIGN(q, k, v, out, lse);
   AttnArgs a{q, k, v, nullptr, nullptr, nullptr, nullptr, dm.N, out, lse, true, nullptr};
   return run_attention(dm, a, stream, "dense_attention");
 }

@@ -111,6 +111,24 @@ def test_null_and_range_arguments():
     assert lib.pisa_select(ctypes.byref(big), FAKE, FAKE, None, 4, FAKE, None, FAKE, 1 << 60, None) == pisa.PISA_UNSUPPORTED
 
 
+def test_misaligned_pointers_are_rejected():
+    """The kernels move 16 bytes per lane; a pointer off a 16-byte boundary is refused on the
+    host, before any launch."""
+    lib = pisa.raw()
+    s = shape()
+    odd = ctypes.c_void_p(FAKE.value + 2)
+    assert lib.dense_attention(ctypes.byref(s), FAKE, odd, FAKE, FAKE, None, None) == pisa.PISA_INVALID_ARG
+    assert "aligned" in pisa.last_error()
+    assert lib.pisa_attention(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 4, odd, None, FAKE, 1 << 40,
+                              None) == pisa.PISA_INVALID_ARG
+    assert "aligned" in pisa.last_error()
+    assert lib.pisa_select(ctypes.byref(s), FAKE, FAKE, None, 4, FAKE, None, odd, 1 << 40, None) == pisa.PISA_INVALID_ARG
+    assert lib.pisa_block_stats(ctypes.byref(s), odd, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 40,
+                                None) == pisa.PISA_INVALID_ARG
+    assert lib.pisa_block_heterogeneity(ctypes.byref(s), FAKE, FAKE, FAKE, 1, 1e-6, odd, FAKE, 1 << 40, None) \
+        == pisa.PISA_INVALID_ARG
+
+
 def test_binding_refuses_host_tensors():
     import torch
     q = torch.zeros(1, 2, 128, 64)
