@@ -57,8 +57,14 @@ static int32_t resolve(const pisa_shape* s, Dims* dm) {
 }
 
 StatsPlan stats_plan(const Dims& dm) {
-  // Aim at about 1024 workgroups over the whole launch.
-  int want = (1024 + dm.bh() - 1) / dm.bh();
+  // The streaming kernels keep two workgroups on each of the 256 compute units, and all
+  // their workgroups take about the same time: the launch should be a whole number of rounds
+  // of 512, never a few workgroups more.  Aim at two rounds (one when that still leaves a
+  // workgroup only a handful of blocks, to halve the partial sums written and re-read).
+  const int kSlots = 512;
+  int target = 2 * kSlots;
+  if ((long long)dm.N * dm.bh() <= 8LL * kSlots) target = kSlots;
+  int want = target / dm.bh();
   if (want < 1) want = 1;
   if (want > dm.N) want = dm.N;
   StatsPlan p;

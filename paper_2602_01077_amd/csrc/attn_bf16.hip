@@ -82,8 +82,9 @@ __device__ inline void split_bf16(float x, unsigned int& hi, unsigned int& lo) {
 
 // ---------------------------------------------------------------------------------
 // Pre-pass for PISA: centroid tiles and hsum in the forms the main kernel consumes.
-// grid (npad/64 + 1, bh); the extra block of each head packs hsum.
+// grid (npad/64 + kPackBlocks, bh); the extra blocks of each head pack hsum.
 // ---------------------------------------------------------------------------------
+constexpr int kPackBlocks = 8;
 __global__ __launch_bounds__(256) void attn_prep_kernel(
     const float* __restrict__ kbar, const float* __restrict__ vsum, const float* __restrict__ hsum,
     __bf16* __restrict__ kcen, __bf16* __restrict__ vbar,
@@ -120,15 +121,25 @@ __global__ __launch_bounds__(256) void attn_prep_kernel(
       bias[j] = j < N ? __builtin_amdgcn_logf((float)(j == N - 1 ? last_rows : B)) : -INFINITY;
     }
   } else if (hsum) {
-    // hpack[part][ks][dt][lane][e] = part(hsum[d_in = 16 ks + 8 h + e][d_out = 32 dt + lam])
+    // hpack[part][ks][dt][lane][e] = part(hsum[d_in = 16 ks + 8 h + e][d_out = 32 dt + lam]);
+    // each of the kPackBlocks extra blocks of a head packs one slice of the d x d matrix.
     const float* hs = hsum + bh * (size_t)D * D;
     __bf16* hp = hpack + bh * (size_t)(2 * D * D);
-    for (int o = tid; o < D * D; o += 256) {
+    constexpr int PER = D * D / kPackBlocks / 256;      // elements per thread
+    const int o0 = (g - npad / kTile) * (D * D / kPackBlocks) + tid;
+    float x[PER];
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+      const int o = o0 + 256 * u;
       const int e = o & 7, lane = (o >> 3) & 63, dt = (o >> 9) & 3, ks = o >> 11;
       const int lam = lane & 31, h = lane >> 5;
-      const float x = hs[(size_t)(16 * ks + 8 * h + e) * D + 32 * dt + lam];
+      x[u] = hs[(size_t)(16 * ks + 8 * h + e) * D + 32 * dt + lam];
+    }
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+      const int o = o0 + 256 * u;
       unsigned int hi, lo;
-      split_bf16(x, hi, lo);
+      split_bf16(x[u], hi, lo);
       reinterpret_cast<unsigned short*>(hp)[o] = (unsigned short)hi;
       reinterpret_cast<unsigned short*>(hp)[D * D + o] = (unsigned short)lo;
     }
@@ -738,7 +749,7 @@ hipError_t launch_attention_bf16(const Dims& dm, const AttnArgs& a, hipStream_t 
     __bf16* vbar = kcen + tile_elems;
     __bf16* hpack = vbar + tile_elems;
     float* bias = reinterpret_cast<float*>(hpack + (size_t)dm.bh() * 2 * D * D);
-    hipLaunchKernelGGL(attn_prep_kernel, dim3(p.npad / kTile + 1, dm.bh()), dim3(256), 0, stream,
+    hipLaunchKernelGGL(attn_prep_kernel, dim3(p.npad / kTile + kPackBlocks, dm.bh()), dim3(256), 0, stream,
                        a.kbar, a.vsum, a.hsum, kcen, vbar, bias, hpack, dm.L, dm.B, dm.N, p.npad);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

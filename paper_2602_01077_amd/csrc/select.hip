@@ -96,6 +96,46 @@ __global__ __launch_bounds__(256, 2) void logits_kernel(const double* __restrict
   }
 }
 
+// The same product for short sequences, where 64x64 tiles would leave most of the chip
+// idle: one wave per 16x16 tile, all operand loads issued up front.
+template <int D>
+__global__ __launch_bounds__(256) void logits_small_kernel(const double* __restrict__ qbar64,
+                                                           const double* __restrict__ kbar64,
+                                                           const double* __restrict__ col_bias,
+                                                           double* __restrict__ z, int N, double scale) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const size_t bh = blockIdx.z;
+  const int i0 = blockIdx.y * 16;
+  const int j0 = (blockIdx.x * 4 + wave) * 16;
+  if (j0 >= N) return;                     // whole wave; the kernel has no barriers
+  const int r = lane & 15, kk = lane >> 4;
+  const double* qp = qbar64 + (bh * N + min(i0 + r, N - 1)) * (size_t)D + 4 * kk;
+  const double* kp = kbar64 + (bh * N + min(j0 + r, N - 1)) * (size_t)D + 4 * kk;
+  f64x4 av[D / 16], bv[D / 16];
+#pragma unroll
+  for (int c = 0; c < D / 16; ++c) {
+    av[c] = *reinterpret_cast<const f64x4*>(qp + 16 * c);
+    bv[c] = *reinterpret_cast<const f64x4*>(kp + 16 * c);
+  }
+  f64x4 acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = acc0;
+#pragma unroll
+  for (int c = 0; c < D / 16; ++c)
+#pragma unroll
+    for (int u = 0; u < 4; u += 2) {
+      acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64(av[c][u], bv[c][u], acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64(av[c][u + 1], bv[c][u + 1], acc1, 0, 0, 0);
+    }
+  const int j = j0 + r;
+  if (j >= N) return;
+  const double bias = col_bias ? col_bias[bh * N + j] : 0.0;
+  double* zb = z + bh * (size_t)N * N;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int i = i0 + 4 * e + kk;
+    if (i < N) zb[(size_t)i * N + j] = scale * (acc0[e] + acc1[e]) + bias;
+  }
+}
+
 __device__ inline unsigned long long order_key(double x) {
   unsigned long long u = (unsigned long long)__double_as_longlong(x);
   return (u >> 63) ? ~u : (u | 0x8000000000000000ull);
@@ -271,13 +311,24 @@ hipError_t launch_select(const Dims& dm, const double* qbar64, const double* kba
                          const double* col_bias, int k_top, int32_t* idx, float* kth_gap, double* zbuf,
                          hipStream_t stream) {
   const int nt = (dm.N + kZT - 1) / kZT;
-  const dim3 zgrid((nt + 3) / 4, nt, dm.bh());
-  if (dm.d == 64)
-    hipLaunchKernelGGL(logits_kernel<64>, zgrid, dim3(256), 0, stream, qbar64, kbar64, col_bias, zbuf, dm.N,
-                       (double)dm.scale);
-  else
-    hipLaunchKernelGGL(logits_kernel<128>, zgrid, dim3(256), 0, stream, qbar64, kbar64, col_bias, zbuf, dm.N,
-                       (double)dm.scale);
+  if ((size_t)nt * nt * dm.bh() < 1024) {                 // too few 64x64 tiles to fill the chip
+    const int nt16 = (dm.N + 15) / 16;
+    const dim3 sgrid((nt16 + 3) / 4, nt16, dm.bh());
+    if (dm.d == 64)
+      hipLaunchKernelGGL(logits_small_kernel<64>, sgrid, dim3(256), 0, stream, qbar64, kbar64, col_bias, zbuf,
+                         dm.N, (double)dm.scale);
+    else
+      hipLaunchKernelGGL(logits_small_kernel<128>, sgrid, dim3(256), 0, stream, qbar64, kbar64, col_bias, zbuf,
+                         dm.N, (double)dm.scale);
+  } else {
+    const dim3 zgrid((nt + 3) / 4, nt, dm.bh());
+    if (dm.d == 64)
+      hipLaunchKernelGGL(logits_kernel<64>, zgrid, dim3(256), 0, stream, qbar64, kbar64, col_bias, zbuf, dm.N,
+                         (double)dm.scale);
+    else
+      hipLaunchKernelGGL(logits_kernel<128>, zgrid, dim3(256), 0, stream, qbar64, kbar64, col_bias, zbuf, dm.N,
+                         (double)dm.scale);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const size_t n_rows = (size_t)dm.bh() * dm.N;

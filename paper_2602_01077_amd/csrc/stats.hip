@@ -127,7 +127,15 @@ __global__ __launch_bounds__(256) void reduce_h_kernel(const float* __restrict__
   if (e >= dd) return;
   const float* p = partial_h + bh * n_chunks * (size_t)dd + e;
   float acc = 0.f;
-  for (int c = 0; c < n_chunks; ++c) acc += p[(size_t)c * dd];
+  int c = 0;
+  for (; c + 8 <= n_chunks; c += 8) {         // eight loads in flight, added in chunk order
+    float x[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) x[u] = p[(size_t)(c + u) * dd];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc += x[u];
+  }
+  for (; c < n_chunks; ++c) acc += p[(size_t)c * dd];
   hsum[bh * dd + e] = acc;
 }
 

@@ -3,7 +3,8 @@
 // Grid (n_chunks, batch*heads); a workgroup of 4 waves walks `chunk_blocks` consecutive
 // blocks of one head.  Per 64-token (sub-)block:
 //   * wave w loads rows 16w..16w+15 of the Q, K and V tiles, one 4-byte channel pair per
-//     lane (a wave-load is one 256-byte row), and adds them in fp64 (exact for bf16 data);
+//     lane (a wave-load is one 256-byte row), one sub-block ahead of their use, and adds
+//     them in fp64 (exact for bf16 data);
 //     the four waves' partial column sums meet in LDS and are added in wave order;
 //   * K is centred on the block mean in registers, split into bf16 hi + lo parts and
 //     written to LDS together with V (rows swizzled for conflict-free transposed reads);
@@ -83,7 +84,8 @@ __global__ __launch_bounds__(256, 2) void stats_bf16_kernel(
   __shared__ float dks[2][D];           // c_s - kbar_j
   __shared__ float kmean_s[D];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: row addresses stay scalar
   const int chunk = blockIdx.x;
   const size_t bh = blockIdx.y;
   const size_t head_words = (size_t)L * (D / 2);
@@ -99,8 +101,26 @@ __global__ __launch_bounds__(256, 2) void stats_bf16_kernel(
 #pragma unroll
   for (int bt = 0; bt < 4; ++bt) acc[bt] = (f32x16){0};
 
+  // This wave's 16 rows of one 64-token sub-block, one channel pair per lane.  Rows past the
+  // end repeat the last valid row (the users mask them), so the loads carry no conditions.
+  auto load_rows = [&](const unsigned int* src, int row0, int rows, unsigned int (&x)[16]) {
+    if (rows <= 0) return;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) x[i] = src[(size_t)(row0 + min(16 * wave + i, rows - 1)) * (D / 2) + lane];
+  };
+
   const int j_begin = chunk * chunk_blocks;
   const int j_end = min(N, j_begin + chunk_blocks);
+  // The rows of sub-block t + 1 are requested while sub-block t is worked on (K and V at its
+  // start into a second register set, Q into its own registers once its sums are taken), so a
+  // wave always has 8 to 12 KB of loads in flight.
+  unsigned int kx[16] = {}, vx[16] = {}, qx[16] = {}, kn[16] = {}, vn[16] = {};
+  if (j_begin < j_end) {
+    const int rows = min(kTile, L - j_begin * B);
+    load_rows(qh, j_begin * B, rows, qx);
+    load_rows(kh, j_begin * B, rows, kx);
+    load_rows(vh, j_begin * B, rows, vx);
+  }
   for (int j = j_begin; j < j_end; ++j) {
     const int block_rows = min(B, L - j * B);
     int n_sub = 0;
@@ -109,23 +129,25 @@ __global__ __launch_bounds__(256, 2) void stats_bf16_kernel(
       const int rows = min(kTile, L - row0);
       if (rows <= 0) break;                       // uniform: the block ends inside its first half
       n_sub = sub + 1;
-      // ---- load this wave's 16 rows, one channel pair per lane ----
-      unsigned int kx[16], vx[16], qx[16];
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int n = 16 * wave + i;
-        kx[i] = vx[i] = qx[i] = 0u;
-        if (n < rows) {
-          const size_t o = (size_t)(row0 + n) * (D / 2) + lane;
-          qx[i] = qh[o];
-          kx[i] = kh[o];
-          vx[i] = vh[o];
+      int next_row0, next_rows;
+      {
+        int nj = j, ns = sub + 1;
+        if (ns == TPB || j * B + ns * kTile >= L) {
+          nj = j + 1;
+          ns = 0;
         }
+        next_row0 = nj * B + ns * kTile;
+        next_rows = nj < j_end ? min(kTile, L - next_row0) : 0;
+        load_rows(kh, next_row0, next_rows, kn);
+        load_rows(vh, next_row0, next_rows, vn);
       }
-      // ---- fp64 column sums of the 16 rows (zeros of absent rows add nothing) ----
+      // ---- fp64 column sums of the 16 rows (absent rows are zeroed first) ----
       double sq0 = 0, sq1 = 0, sk0 = 0, sk1 = 0, sv0 = 0, sv1 = 0;
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
+        if (16 * wave + i >= rows) {              // uniform
+          qx[i] = kx[i] = vx[i] = 0u;
+        }
         sq0 += (double)__uint_as_float(qx[i] << 16);
         sq1 += (double)__uint_as_float(qx[i] & 0xffff0000u);
         sk0 += (double)__uint_as_float(kx[i] << 16);
@@ -136,6 +158,7 @@ __global__ __launch_bounds__(256, 2) void stats_bf16_kernel(
       *reinterpret_cast<f64x2*>(&red[0][wave][2 * lane]) = (f64x2){sq0, sq1};
       *reinterpret_cast<f64x2*>(&red[1][wave][2 * lane]) = (f64x2){sk0, sk1};
       *reinterpret_cast<f64x2*>(&red[2][wave][2 * lane]) = (f64x2){sv0, sv1};
+      load_rows(qh, next_row0, next_rows, qx);    // Q(t) is used up
       __syncthreads();
       if (tid < D) {
         const double sq = ((red[0][0][tid] + red[0][1][tid]) + red[0][2][tid]) + red[0][3][tid];
@@ -193,6 +216,11 @@ __global__ __launch_bounds__(256, 2) void stats_bf16_kernel(
         }
       }
       // the next sub-block's LDS writes are separated from these reads by its two barriers
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        kx[i] = kn[i];
+        vx[i] = vn[i];
+      }
     }
     if (TPB == 2) {
       // ---- block outputs from the sub-block totals, then the rank-one corrections ----
