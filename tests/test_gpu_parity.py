@@ -404,6 +404,37 @@ def test_video_configs_sampled(lib, name):
           f"index rows differing at tiny gaps: {soft_total}")
 
 
+@pytest.mark.parametrize("block,L", [(64, 4096 * 64 - 37), (128, 4096 * 128)])
+def test_maximum_block_count(lib, block, L):
+    """N = 4096 blocks, the most the selection and the block bitmasks are sized for (one head;
+    block 64 with a ragged last block, block 128 exact): statistics and index sets in full,
+    outputs on sampled query blocks including the first and the last."""
+    w = WORKLOADS["wan"].with_(name=f"max-blocks-{block}", heads=1, seq_len=L, block=block, grid=None,
+                               sparsity=0.98)
+    assert w.num_blocks == 4096
+    scale = lib.resolved_scale(w.head_dim)
+    q, k, v = make_qkv(w, device=DEV)
+    res = lib.pisa_forward(q, k, v, block, w.sparsity, want_lse=True)
+    dense, _ = lib.dense_attention(q, k, v, block)
+    torch.cuda.synchronize()
+    N, k_top = w.num_blocks, w.topk
+    Q, K, V, st, idx_ref, gap_ref = oracle_head(q, k, v, 0, block, scale, k_top)
+    check_stats(res["stats"], st, 0, q.dtype)
+    idx_gpu = res["idx"][0, 0].cpu().numpy()
+    soft = check_select(idx_gpu, res["kth_gap"][0, 0].cpu().numpy().astype(np.float64), idx_ref, gap_ref, N,
+                        where=f" {w.name}")
+    blocks = [0, 1, 2047, 2048, 4094, 4095]
+    rows = rows_of_blocks(blocks, block, L)
+    ref, _ = po.attention_head(Q, K, V, block, idx_gpu, scale, "hybrid", blocks=blocks, stats=st)
+    rel, cos = row_errors(res["out"][0, 0].float().cpu().numpy()[rows], ref)
+    dref, _ = po.attention_head(Q, K, V, block, None, scale, "dense", blocks=blocks)
+    drel, dcos = row_errors(dense[0, 0].float().cpu().numpy()[rows], dref)
+    print(f"[parity] {w.name} L={L} k={k_top}: pisa {rel:.2e} dense {drel:.2e} cos_min {min(cos, dcos):.6f} "
+          f"index rows differing at tiny gaps: {len(soft)}")
+    assert rel <= TOL[q.dtype] and cos >= COS_MIN
+    assert drel <= TOL[q.dtype] and dcos >= COS_MIN
+
+
 @pytest.mark.parametrize("block,r", [(64, 0.0), (64, 0.5), (64, 0.75), (64, 0.95), (128, 0.85)])
 def test_wan_sweep_sampled(lib, block, r):
     """Sparsity / block-size sweep at the Wan shape (r = 0.85, block 64 is the test above).
