@@ -84,6 +84,7 @@ size_t pisa_workspace_bytes(const pisa_shape* shape);
  *                with value channel b)
  *   qbar64, kbar64: the same means in fp64 [batch,heads,N,d] (block sums are accumulated
  *                in fp64, so for bf16 inputs they are exact); pisa_select ranks with these.
+ *                Either may be NULL when the caller does not need it.
  * Outputs are written, never read.  `workspace` must hold pisa_workspace_bytes(shape).
  */
 int32_t pisa_block_stats(const pisa_shape* shape, const void* q, const void* k, const void* v,
@@ -139,8 +140,11 @@ int32_t pisa_select(const pisa_shape* shape, const double* qbar64, const double*
  *            drops the approximation altogether: plain block-sparse "keep-or-drop" attention
  *            over S_i (Preliminaries, second equation; the ablation's baseline curve);
  *            k_top must then be >= 1.
- *   idx      int32 [batch,heads,N,k_top]; must be in range, ascending and unique within a
- *            row (as pisa_select writes it) -- contents are not checked on the device.
+ *   idx      int32 [batch,heads,N,k_top]; expected in range, ascending and unique within a
+ *            row (as pisa_select writes it).  The kernels never index memory with an entry
+ *            outside [0, N): such entries are ignored (the row then attends fewer blocks
+ *            exactly).  Order does not matter to the bf16 build; a repeated entry is
+ *            harmless there and counts the block twice in the fp32 build.
  *   out      [batch,heads,seq_len,d] in shape->dtype
  *   lse      fp32 [batch,heads,seq_len]: log D_t; may be NULL.
  * k_top == N reproduces dense_attention; k_top == 0 is the pure approximation.

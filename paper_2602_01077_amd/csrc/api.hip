@@ -122,8 +122,8 @@ int32_t pisa_block_stats(const pisa_shape* shape, const void* q, const void* k, 
   int32_t rc = resolve(shape, &dm);
   if (rc != PISA_OK) return rc;
   if (!q || !k || !v) return fail(PISA_INVALID_ARG, "q, k, v must not be NULL");
-  if (!qbar || !kbar || !vsum || !hsum || !qbar64 || !kbar64)
-    return fail(PISA_INVALID_ARG, "qbar, kbar, vsum, hsum, qbar64, kbar64 must not be NULL");
+  if (!qbar || !kbar || !vsum || !hsum)
+    return fail(PISA_INVALID_ARG, "qbar, kbar, vsum, hsum must not be NULL");
   PISA_CHECK_ALIGN(q, k, v, qbar, kbar, vsum, hsum, qbar64, kbar64, workspace);
   size_t need = stats_workspace_bytes(dm);
   if (!workspace) return fail(PISA_INVALID_ARG, "workspace is NULL (need %zu bytes)", need);

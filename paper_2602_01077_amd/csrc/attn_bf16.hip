@@ -504,7 +504,8 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
         const int32_t* row = p.idx + (bh * N + i) * (size_t)p.k_top;
         for (int t = tid; t < p.k_top; t += 256) {
           const int j = row[t];
-          atomicOr(&chosen[b][j >> 5], 1u << (j & 31));
+          if ((unsigned)j < (unsigned)N)          // entries outside [0, N) are ignored
+            atomicOr(&chosen[b][j >> 5], 1u << (j & 31));
         }
       }
     }

@@ -62,7 +62,7 @@ __global__ __launch_bounds__(256) void attn_fp32_kernel(P32 p) {
   if (!p.dense)
     for (int t = tid; t < p.k_top; t += 256) {
       const int j = my_idx[t];
-      atomicOr(&chosen[j >> 5], 1u << (j & 31));
+      if ((unsigned)j < (unsigned)N) atomicOr(&chosen[j >> 5], 1u << (j & 31));   // others are ignored
     }
 
   float o[DQ];
@@ -132,7 +132,9 @@ __global__ __launch_bounds__(256) void attn_fp32_kernel(P32 p) {
   // ---- Phase 1: exact tiles ----
   const int n_exact_tiles = p.dense ? (L + kTile - 1) / kTile : p.k_top * tpb;
   for (int t = 0; t < n_exact_tiles; ++t) {
-    const int tile = p.dense ? t : my_idx[t / tpb] * tpb + t % tpb;
+    const int jsel = p.dense ? 0 : my_idx[t / tpb];
+    if ((unsigned)jsel >= (unsigned)N) continue;          // uniform: entries outside [0, N) are ignored
+    const int tile = p.dense ? t : jsel * tpb + t % tpb;
     const int row0 = tile * kTile;
     const int nvalid = min(kTile, L - row0);
     if (nvalid <= 0) continue;

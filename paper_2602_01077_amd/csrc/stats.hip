@@ -78,8 +78,8 @@ __global__ __launch_bounds__(256) void stats_kernel(
       qbar[o] = (float)qm;
       kbar[o] = (float)km;
       vsum[o] = (float)sv;
-      qbar64[o] = qm;
-      kbar64[o] = km;
+      if (qbar64) qbar64[o] = qm;
+      if (kbar64) kbar64[o] = km;
       kmean[tid] = km;
     }
     __syncthreads();

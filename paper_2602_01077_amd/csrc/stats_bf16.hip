@@ -171,8 +171,8 @@ __global__ __launch_bounds__(256, 2) void stats_bf16_kernel(
           qbar[o] = (float)qm;
           kbar[o] = (float)cm;
           vsum[o] = (float)sv;
-          qbar64[o] = qm;
-          kbar64[o] = cm;
+          if (qbar64) qbar64[o] = qm;
+          if (kbar64) kbar64[o] = cm;
         } else {
           tot[0][tid] = sub == 0 ? sq : tot[0][tid] + sq;
           tot[1][tid] = sub == 0 ? sk : tot[1][tid] + sk;
@@ -230,8 +230,8 @@ __global__ __launch_bounds__(256, 2) void stats_bf16_kernel(
         qbar[o] = (float)qm;
         kbar[o] = (float)km;
         vsum[o] = (float)tot[2][tid];
-        qbar64[o] = qm;
-        kbar64[o] = km;
+        if (qbar64) qbar64[o] = qm;
+        if (kbar64) kbar64[o] = km;
         for (int sub = 0; sub < n_sub; ++sub) dks[sub][tid] = (float)(csub[sub][tid] - km);
       }
       __syncthreads();

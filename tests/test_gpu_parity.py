@@ -285,6 +285,22 @@ def test_stats_are_run_to_run_identical(lib):
         assert torch.equal(a[name], b[name]), name
 
 
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("fp32", 64)])
+def test_stats_without_fp64_means(lib, dtype, d):
+    """qbar64 / kbar64 are optional outputs of pisa_block_stats: leaving them out must not
+    change the others."""
+    w = WORKLOADS["flux"].with_(heads=2, seq_len=1000, head_dim=d, dtype=dtype, grid=None)
+    q, k, v = (x.to(DEV) for x in make_qkv(w))
+    shape = lib.make_shape(q, 64)
+    ws = lib.alloc_workspace(shape, DEV)
+    full = lib.block_stats(q, k, v, 64, ws)
+    part = {n: (None if n.endswith("64") else torch.full_like(t, float("nan"))) for n, t in full.items()}
+    lib.block_stats_into(shape, q, k, v, part, ws)
+    torch.cuda.synchronize()
+    for n in ("qbar", "kbar", "vsum", "hsum"):
+        assert torch.equal(full[n], part[n]), n
+
+
 def test_select_ties_and_duplicates(lib):
     """Duplicate centroids give exactly equal logits: the lower index must win, and
     the reported gap is zero there."""
@@ -311,6 +327,35 @@ def test_select_ties_and_duplicates(lib):
                     # only legal if the sets carry the same logit multiset (fp64 rounding of z itself)
                     assert np.allclose(np.sort(z[i, got[i]]), np.sort(z[i, ref[i]]), atol=1e-12), (k_top, h, i)
             assert np.abs(gap[0, h].cpu().numpy() - gref).max() < 1e-5
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("fp32", 64)])
+def test_out_of_range_index_entries_are_ignored(lib, dtype, d):
+    """pisa_attention cannot validate device-side index lists: entries outside [0, N) must be
+    skipped by the kernels' own range checks, leaving the attention over the remaining blocks."""
+    w = WORKLOADS["tiny" if dtype == "fp32" else "flux"].with_(name="badidx", heads=2, seq_len=1500, head_dim=d,
+                                                             dtype=dtype, grid=None, sparsity=0.7)
+    q, k, v = make_qkv(w, device="cpu")
+    qd, kd, vd = q.to(DEV), k.to(DEV), v.to(DEV)
+    shape = lib.make_shape(qd, w.block)
+    scale = lib.resolved_scale(d)
+    ws = lib.alloc_workspace(shape, DEV)
+    st = lib.block_stats(qd, kd, vd, w.block, ws)
+    N, k_top = w.num_blocks, w.topk
+    idx, _ = lib.select(shape, st["qbar64"], st["kbar64"], k_top, ws)
+    bad = idx.clone()
+    bad[..., -1] = N + 7                 # past the end
+    bad[..., -2] = -3                    # negative
+    bad[..., -3] = 2 ** 31 - 1           # huge
+    out, _ = lib.attention(shape, qd, kd, vd, st["kbar"], st["vsum"], st["hsum"], bad, k_top, workspace=ws)
+    torch.cuda.synchronize()
+    kept = idx[..., : k_top - 3].contiguous()
+    for h in range(w.heads):
+        Q, K, V = head_np(q, 0, h), head_np(k, 0, h), head_np(v, 0, h)
+        ost = po.block_stats(Q, K, V, w.block)
+        ref, _ = po.attention_head(Q, K, V, w.block, kept[0, h].cpu().numpy(), scale, "hybrid", stats=ost)
+        rel, cos = row_errors(out[0, h].float().cpu().numpy(), ref)
+        assert rel <= TOL[q.dtype] and cos >= COS_MIN, (dtype, h, rel, cos)
 
 
 @pytest.mark.parametrize("N", [65, 512, 513, 1280, 1281, 2049, 4096])
