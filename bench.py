@@ -81,6 +81,7 @@ def main():
     ap.add_argument("--block", type=int, default=None)
     ap.add_argument("--dense-steps", type=int, default=3, help="timed dense_attention calls (0 = skip)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--no-probe", action="store_true", help="skip the measured-peak probes (MFMA loop, 1 GiB copy)")
     ap.add_argument("--covariance-aware", choices=["spectral", "frobenius"], default=None,
                     help="add the covariance-aware selection score (pisa_block_heterogeneity) to the step")
     ap.add_argument("--copy-calibration", type=int, default=0,
@@ -174,6 +175,33 @@ def main():
     else:
         l1_vs_dense = None
 
+    # What this chip sustains on its own: the matrix instruction in a register-only loop, and a
+    # plain 1 GiB device copy (read + write), to quote beside the published peaks.
+    measured = None
+    if not args.no_probe:
+        sink = torch.empty(1 << 18, dtype=torch.float32, device=dev)
+        pisa.probe_mfma_rate(500, sink)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        flop = pisa.probe_mfma_rate(8000, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        mfma_tf = flop / (e0.elapsed_time(e1) * 1e-3) / 1e12
+        csrc = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        cdst = torch.empty_like(csrc)
+        cdst.copy_(csrc)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(3):
+            cdst.copy_(csrc)
+        e1.record()
+        torch.cuda.synchronize()
+        copy_gbps = 3 * 2 * csrc.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        del csrc, cdst
+        measured = {"mfma_bf16_TFLOPs": round(mfma_tf, 1), "copy_GBps": round(copy_gbps, 1)}
+        note(f"measured peaks: {measured}")
+
     if args.copy_calibration > 0:
         # int32 add-one over 1 GiB: an elementwise kernel that reads 1 GiB and writes 1 GiB
         src = torch.ones(1 << 28, dtype=torch.int32, device=dev)
@@ -223,7 +251,12 @@ def main():
         "roofline": {"kernel": "attn_bf16_kernel (pisa_attention)", "bound": "mfma",
                      "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": traffic},
+        "measured_peaks": measured,
     }
+    if measured:
+        result["roofline"]["frac_of_measured_mfma_rate"] = round(achieved / measured["mfma_bf16_TFLOPs"], 4)
+        result["stats_frac_of_measured_copy"] = round(
+            in_bytes / (stage[0] * 1e-3) / 1e9 / measured["copy_GBps"], 4)
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(w, q, k, v, scale, k_top)
     print(json.dumps(result), flush=True)

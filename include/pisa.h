@@ -162,6 +162,16 @@ int32_t pisa_attention(const pisa_shape* shape, const void* q, const void* k, co
 int32_t dense_attention(const pisa_shape* shape, const void* q, const void* k, const void* v,
                         void* out, float* lse, void* stream);
 
+/*
+ * Measurement aid, not a step of the method: enqueues a register-only loop of the bf16
+ * matrix instruction the attention kernels use (1024 workgroups x 4 waves x iters x 16
+ * MFMAs of 32x32x16) and stores the floating-point operation count in *flop (host memory).
+ * The caller times the launch on `stream`; flop / time is the matrix-core rate the chip
+ * sustains at its own clock, to quote beside the published peak.  `sink` is device memory of
+ * at least 262144 floats (overwritten).  iters in [1, 2^24].
+ */
+int32_t pisa_probe_mfma_rate(int32_t iters, float* sink, size_t sink_floats, double* flop, void* stream);
+
 /* Message of the last failure on this thread ("" if none).  Never NULL. */
 const char* pisa_last_error(void);
 

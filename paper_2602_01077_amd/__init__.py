@@ -22,7 +22,8 @@ PISA_FP32, PISA_BF16 = 0, 1
 PISA_NORM_SPECTRAL, PISA_NORM_FROBENIUS = 0, 1
 
 EXPORTS = ("pisa_num_blocks", "pisa_topk_count", "pisa_workspace_bytes", "pisa_block_stats",
-           "pisa_block_heterogeneity", "pisa_select", "pisa_attention", "dense_attention", "pisa_last_error")
+           "pisa_block_heterogeneity", "pisa_select", "pisa_attention", "dense_attention",
+           "pisa_probe_mfma_rate", "pisa_last_error")
 
 
 class PisaShape(ctypes.Structure):
@@ -41,7 +42,7 @@ class PisaError(RuntimeError):
 def _load() -> ctypes.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(
-            f"{LIB_PATH} is missing: build it with `python -m paper_2602_01077_amd.build` "
+            f"{LIB_PATH} is missing: build it with `python paper_2602_01077_amd/build.py` "
             "(there is no fallback implementation)")
     lib = ctypes.CDLL(LIB_PATH)
     vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
@@ -62,6 +63,8 @@ def _load() -> ctypes.CDLL:
     lib.pisa_attention.restype = i32
     lib.dense_attention.argtypes = [shp, vp, vp, vp, vp, vp, vp]
     lib.dense_attention.restype = i32
+    lib.pisa_probe_mfma_rate.argtypes = [i32, vp, sz, ctypes.POINTER(ctypes.c_double), vp]
+    lib.pisa_probe_mfma_rate.restype = i32
     lib.pisa_last_error.argtypes = []
     lib.pisa_last_error.restype = ctypes.c_char_p
     return lib
@@ -233,6 +236,15 @@ def dense_attention(q, k, v, block: int = 64, scale: Optional[float] = None,
         ctypes.byref(shape), _dev(q, "q"), _dev(k, "k", like=q), _dev(v, "v", like=q),
         _dev(out, "out", like=q), _dev(lse, "lse", torch.float32), _stream()))
     return out, lse
+
+
+def probe_mfma_rate(iters: int, sink: torch.Tensor) -> float:
+    """pisa_probe_mfma_rate: enqueues the matrix-instruction loop; returns its flop count
+    (the caller times the launch)."""
+    flop = ctypes.c_double(0.0)
+    _check(_lib.pisa_probe_mfma_rate(iters, _dev(sink, "sink", torch.float32), sink.numel(), ctypes.byref(flop),
+                                     _stream()))
+    return flop.value
 
 
 def pisa_forward(q, k, v, block: int = 64, sparsity: float = 0.85, first_order: bool = True,

@@ -9,7 +9,8 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libpisa.so")
-SOURCES = ["api.hip", "stats.hip", "stats_bf16.hip", "select.hip", "hetero.hip", "attn_fp32.hip", "attn_bf16.hip"]
+SOURCES = ["api.hip", "stats.hip", "stats_bf16.hip", "select.hip", "hetero.hip", "attn_fp32.hip", "attn_bf16.hip",
+           "probe.hip"]
 
 
 def hipcc() -> str:

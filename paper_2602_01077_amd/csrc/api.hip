@@ -227,6 +227,18 @@ int32_t dense_attention(const pisa_shape* shape, const void* q, const void* k, c
   return run_attention(dm, a, stream, "dense_attention");
 }
 
+int32_t pisa_probe_mfma_rate(int32_t iters, float* sink, size_t sink_floats, double* flop, void* stream) {
+  if (iters < 1 || iters > (1 << 24)) return fail(PISA_INVALID_ARG, "iters = %d outside [1, 2^24]", iters);
+  if (!sink || !flop) return fail(PISA_INVALID_ARG, "sink and flop must not be NULL");
+  const size_t need = (size_t)kProbeWorkgroups * 256;
+  if (sink_floats < need) return fail(PISA_WORKSPACE_TOO_SMALL, "sink has %zu floats, need %zu", sink_floats, need);
+  PISA_CHECK_ALIGN(sink);
+  *flop = (double)kProbeWorkgroups * 4.0 * (double)iters * 16.0 * (2.0 * 32 * 32 * 16);
+  hipError_t e = launch_mfma_probe(iters, sink, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail("pisa_probe_mfma_rate", e);
+  return PISA_OK;
+}
+
 const char* pisa_last_error(void) { return pisa::g_err; }
 
 }  // extern "C"

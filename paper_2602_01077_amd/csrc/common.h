@@ -70,4 +70,8 @@ size_t attention_workspace_bytes(const Dims& dm);
 hipError_t launch_attention_fp32(const Dims& dm, const AttnArgs& a, hipStream_t stream);
 hipError_t launch_attention_bf16(const Dims& dm, const AttnArgs& a, hipStream_t stream);
 
+// Matrix-core rate probe: kProbeWorkgroups workgroups of 4 waves, 16 MFMAs per wave and iteration.
+constexpr int kProbeWorkgroups = 1024;
+hipError_t launch_mfma_probe(int iters, float* sink, hipStream_t stream);
+
 }  // namespace pisa
