@@ -249,14 +249,14 @@ def probe_mfma_rate(iters: int, sink: torch.Tensor) -> float:
 
 def pisa_forward(q, k, v, block: int = 64, sparsity: float = 0.85, first_order: bool = True,
                  want_lse: bool = False, approximate: bool = True, covariance_aware: bool = False,
-                 norm: int = PISA_NORM_SPECTRAL, eps: float = 1e-6):
+                 norm: int = PISA_NORM_SPECTRAL, eps: float = 1e-6, scale: Optional[float] = None):
     """The whole hot path: block_stats -> select -> attention.
 
     first_order=False gives the zeroth-order variant, approximate=False plain block-sparse
     attention over the selected blocks, covariance_aware=True adds log(M_j + eps) to the
     selection score.  Returns dict(out, lse, idx, kth_gap, stats, k_top, log_m).
     """
-    shape = make_shape(q, block)
+    shape = make_shape(q, block, scale)
     n = num_blocks(q.shape[2], block)
     k_top = topk_count(n, sparsity)
     ws = alloc_workspace(shape, q.device)

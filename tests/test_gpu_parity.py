@@ -229,6 +229,33 @@ def test_covariance_aware_selection(lib, dtype, d, B, L):
         assert rel <= TOL[q.dtype] and cos >= COS_MIN
 
 
+@pytest.mark.parametrize("dtype,d,scale", [("bf16", 128, 0.2), ("fp32", 64, 0.05), ("bf16", 128, 0.01)])
+def test_custom_softmax_scale(lib, dtype, d, scale):
+    """pisa_shape.scale other than 1/sqrt(d) must reach the selection logits, both softmax
+    phases, the first-order weight and the dense kernel alike."""
+    w = WORKLOADS["flux"].with_(name=f"scale-{scale}", heads=2, seq_len=1800, head_dim=d, dtype=dtype, grid=None,
+                               sparsity=0.75)
+    q, k, v = make_qkv(w, device="cpu")
+    qd, kd, vd = q.to(DEV), k.to(DEV), v.to(DEV)
+    s32 = lib.resolved_scale(d, scale)
+    res = lib.pisa_forward(qd, kd, vd, w.block, w.sparsity, want_lse=True, scale=scale)
+    dense, _ = lib.dense_attention(qd, kd, vd, w.block, scale=scale)
+    torch.cuda.synchronize()
+    N, k_top = w.num_blocks, w.topk
+    for h in range(w.heads):
+        Q, K, V, st, idx_ref, gap_ref = oracle_head(q, k, v, h, w.block, s32, k_top)
+        idx_gpu = res["idx"][0, h].cpu().numpy()
+        check_select(idx_gpu, res["kth_gap"][0, h].cpu().numpy().astype(np.float64), idx_ref, gap_ref, N,
+                     where=f" scale {scale} head {h}")
+        ref, rlse = po.attention_head(Q, K, V, w.block, idx_gpu, s32, "hybrid", stats=st)
+        rel, cos = row_errors(res["out"][0, h].float().cpu().numpy(), ref)
+        assert rel <= TOL[q.dtype] and cos >= COS_MIN, (scale, h, rel, cos)
+        assert np.abs(res["lse"][0, h].cpu().numpy() - rlse).max() <= (1e-4 if q.dtype == torch.float32 else 2e-2)
+        dref, _ = po.attention_head(Q, K, V, w.block, None, s32, "dense")
+        drel, dcos = row_errors(dense[0, h].float().cpu().numpy(), dref)
+        assert drel <= TOL[q.dtype] and dcos >= COS_MIN, (scale, h, "dense", drel, dcos)
+
+
 @pytest.mark.parametrize("direction", ["rising", "falling", "spike"])
 def test_runaway_maximum(lib, direction):
     """Logits that climb (or drop) by hundreds along the key axis: the bf16 kernel's running
