@@ -229,6 +229,51 @@ def test_covariance_aware_selection(lib, dtype, d, B, L):
         assert rel <= TOL[q.dtype] and cos >= COS_MIN
 
 
+def test_three_calls_replay_from_a_hip_graph(lib):
+    """The library only enqueues kernels on the caller's stream (no allocation, no memset, no
+    synchronisation), so statistics -> selection -> attention can be captured once and
+    replayed: every replay, with eager work and synchronisations in between and inputs changed
+    in place, must reproduce the eager result bit for bit."""
+    w = WORKLOADS["flux"].with_(heads=4, seq_len=3000, grid=None)
+    q, k, v = (x.to(DEV) for x in make_qkv(w))
+    shape = lib.make_shape(q, w.block)
+    N, k_top = w.num_blocks, w.topk
+    ws = lib.alloc_workspace(shape, DEV)
+    st = lib.block_stats(q, k, v, w.block, ws)          # also allocates the output tensors
+    idx = torch.empty(1, w.heads, N, k_top, dtype=torch.int32, device=DEV)
+    gap = torch.empty(1, w.heads, N, dtype=torch.float32, device=DEV)
+    out = torch.empty_like(q)
+
+    def run():
+        lib.block_stats_into(shape, q, k, v, st, ws)
+        lib.select_into(shape, st["qbar64"], st["kbar64"], k_top, idx, gap, ws)
+        lib.attention(shape, q, k, v, st["kbar"], st["vsum"], st["hsum"], idx, k_top, out=out, workspace=ws)
+
+    run()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            run()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        q.mul_(1.0 + 0.25 * rep)                        # new inputs, same buffers
+        v.add_(0.125 * rep)
+        run()
+        torch.cuda.synchronize()
+        want_out, want_idx = out.clone(), idx.clone()
+        out.zero_()
+        idx.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(idx, want_idx), rep
+        assert torch.equal(out, want_out), rep
+
+
 @pytest.mark.parametrize("dtype,d,scale", [("bf16", 128, 0.2), ("fp32", 64, 0.05), ("bf16", 128, 0.01)])
 def test_custom_softmax_scale(lib, dtype, d, scale):
     """pisa_shape.scale other than 1/sqrt(d) must reach the selection logits, both softmax
