@@ -66,19 +66,30 @@ def speed_study(args):
         ws = pisa.alloc_workspace(shape, dev)
         out = torch.empty_like(q)
         dense_ms = _time_ms(lambda: pisa.dense_attention(q, k, v, w.block, out=out), args.iters)
+        st = pisa.block_stats(q, k, v, w.block, ws)          # allocates the statistics tensors once
         for r in args.sparsity:
             k_top = pisa.topk_count(w.num_blocks, r)
+            idx = torch.empty(q.shape[0], q.shape[1], w.num_blocks, k_top, dtype=torch.int32, device=dev)
 
             def path():
-                st = pisa.block_stats(q, k, v, w.block, ws)
-                idx, _ = pisa.select(shape, st["qbar64"], st["kbar64"], k_top, ws, want_gap=False)
+                pisa.block_stats_into(shape, q, k, v, st, ws)
+                pisa.select_into(shape, st["qbar64"], st["kbar64"], k_top, idx, None, ws)
                 pisa.attention(shape, q, k, v, st["kbar"], st["vsum"], st["hsum"], idx, k_top, out=out,
                                workspace=ws)
 
             ms = _time_ms(path, args.iters)
-            print(json.dumps({"shape": "B2-H16-D128", "seq_len": L, "density": round(1 - r, 4),
-                              "k_top": k_top, "dense_ms": round(dense_ms, 4), "pisa_ms": round(ms, 4),
-                              "speedup": round(dense_ms / ms, 3)}), flush=True)
+            row = {"shape": "B2-H16-D128", "seq_len": L, "density": round(1 - r, 4), "k_top": k_top,
+                   "dense_ms": round(dense_ms, 4), "pisa_ms": round(ms, 4), "speedup": round(dense_ms / ms, 3)}
+            if args.graph:                                   # the same six launches replayed from a HIP graph
+                graph = torch.cuda.CUDAGraph()
+                side = torch.cuda.Stream()
+                side.wait_stream(torch.cuda.current_stream())
+                with torch.cuda.stream(side):
+                    with torch.cuda.graph(graph, stream=side):
+                        path()
+                torch.cuda.current_stream().wait_stream(side)
+                row["pisa_graph_ms"] = round(_time_ms(graph.replay, args.iters), 4)
+            print(json.dumps(row), flush=True)
 
 
 def main():
@@ -92,6 +103,7 @@ def main():
     s.add_argument("--lengths", type=int, nargs="+", default=[4096, 8192, 16384, 32768, 65536])
     s.add_argument("--sparsity", type=float, nargs="+", default=[0.3, 0.5, 0.7, 0.875])
     s.add_argument("--iters", type=int, default=5)
+    s.add_argument("--graph", action="store_true", help="also time the path replayed from a captured HIP graph")
     args = ap.parse_args()
     (error_study if args.cmd == "error" else speed_study)(args)
 
