@@ -38,8 +38,6 @@ static int32_t resolve(const pisa_shape* s, Dims* dm) {
     return fail(PISA_INVALID_ARG, "block must be 64 or 128, got %d", s->block);
   if (s->head_dim != 64 && s->head_dim != 128)
     return fail(PISA_INVALID_ARG, "head_dim must be 64 or 128, got %d", s->head_dim);
-  if (s->dtype == PISA_BF16 && s->head_dim != 128)
-    return fail(PISA_UNSUPPORTED, "bf16 is built for head_dim 128 only (got %d)", s->head_dim);
   if (!(s->scale == s->scale) || std::isinf(s->scale))
     return fail(PISA_INVALID_ARG, "scale is not finite");
   long long rows = (long long)s->batch * s->heads * s->seq_len;

@@ -47,9 +47,16 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 #define LDS_PTR(T) __attribute__((address_space(3))) T*
 #define GLB_PTR(T) const __attribute__((address_space(1))) T*
 
-constexpr int D = 128;
-constexpr int ROWB = 256;                    // bytes per staged row
-constexpr int TILEB = kTile * ROWB;          // 16 KB: one staged K or V tile
+// Geometry of a head dimension D (128 or 64): a staged K or V tile is 64 rows of 2 D bytes.
+template <int D> struct Geo {
+  static constexpr int ROWB = 2 * D;               // bytes per staged row
+  static constexpr int TILEB = kTile * ROWB;       // one staged K or V tile (16 KB / 8 KB)
+  static constexpr int NKS = D / 16;               // contraction steps of S^T = K Q^T
+  static constexpr int NDT = D / 32;               // 32-channel tiles of O^T
+  static constexpr int CPR = ROWB / 16;            // 16-byte chunks per row
+  static constexpr int RPL = 1024 / ROWB;          // rows a wave-load (1 KB) covers
+  static constexpr int NLD = kTile / (4 * RPL);    // loads per wave and tile
+};
 constexpr int QROWS = 128;                   // query rows per workgroup
 constexpr int MASK_WORDS = kMaxBlocks / 32;  // 128 words per block bitmask
 
@@ -57,10 +64,10 @@ struct PB {
   const __bf16* q;
   const __bf16* k;
   const __bf16* v;
-  const __bf16* kcen;     // [bh][npad][128] kbar_j rounded to bf16    (pre-pass)
-  const __bf16* vbar;     // [bh][npad][128] vsum_j / B_j
+  const __bf16* kcen;     // [bh][npad][D] kbar_j rounded to bf16    (pre-pass)
+  const __bf16* vbar;     // [bh][npad][D] vsum_j / B_j
   const float* bias;      // [npad] log2 B_j, -inf past N
-  const __bf16* hpack;    // [bh][2][8 ks][4 dt][64 lanes][8] hsum^T hi / lo in A-operand order
+  const __bf16* hpack;    // [bh][2][D/16 ks][D/32 dt][64 lanes][8] hsum^T hi / lo in A-operand order
   const int32_t* idx;
   __bf16* out;
   float* lse;
@@ -85,6 +92,7 @@ __device__ inline void split_bf16(float x, unsigned int& hi, unsigned int& lo) {
 // grid (npad/64 + kPackBlocks, bh); the extra blocks of each head pack hsum.
 // ---------------------------------------------------------------------------------
 constexpr int kPackBlocks = 8;
+template <int D>
 __global__ __launch_bounds__(256) void attn_prep_kernel(
     const float* __restrict__ kbar, const float* __restrict__ vsum, const float* __restrict__ hsum,
     __bf16* __restrict__ kcen, __bf16* __restrict__ vbar,
@@ -92,6 +100,7 @@ __global__ __launch_bounds__(256) void attn_prep_kernel(
   const int tid = threadIdx.x;
   const size_t bh = blockIdx.y;
   const int g = blockIdx.x;
+  constexpr int ROWB = Geo<D>::ROWB, NDT = Geo<D>::NDT;
   const int last_rows = L - (N - 1) * B;
   if (g < npad / kTile) {
     const float* kb = kbar + bh * (size_t)N * D;
@@ -99,9 +108,9 @@ __global__ __launch_bounds__(256) void attn_prep_kernel(
     unsigned char* ok = reinterpret_cast<unsigned char*>(kcen + bh * (size_t)npad * D);
     unsigned char* ov = reinterpret_cast<unsigned char*>(vbar + bh * (size_t)npad * D);
 #pragma unroll
-    for (int it = 0; it < 8; ++it) {
+    for (int it = 0; it < kTile * (D / 4) / 256; ++it) {
       const int ch = it * 256 + tid;
-      const int n = ch >> 5, c4 = (ch & 31) * 4;
+      const int n = ch / (D / 4), c4 = (ch % (D / 4)) * 4;
       const int j = g * kTile + n;
       float4 kv = make_float4(0.f, 0.f, 0.f, 0.f), vv = kv;
       if (j < N) {
@@ -131,7 +140,7 @@ __global__ __launch_bounds__(256) void attn_prep_kernel(
 #pragma unroll
     for (int u = 0; u < PER; ++u) {
       const int o = o0 + 256 * u;
-      const int e = o & 7, lane = (o >> 3) & 63, dt = (o >> 9) & 3, ks = o >> 11;
+      const int e = o & 7, lane = (o >> 3) & 63, dt = (o >> 9) % NDT, ks = (o >> 9) / NDT;
       const int lam = lane & 31, h = lane >> 5;
       x[u] = hs[(size_t)(16 * ks + 8 * h + e) * D + 32 * dt + lam];
     }
@@ -149,17 +158,18 @@ __global__ __launch_bounds__(256) void attn_prep_kernel(
 // ---------------------------------------------------------------------------------
 // Main kernel
 // ---------------------------------------------------------------------------------
-struct State {
-  f32x16 ot[4];      // O^T tiles: ot[dt][r] <-> channel 32 dt + (r/4)*8 + 4h + r%4
+template <int D> struct State {
+  f32x16 ot[D / 32]; // O^T tiles: ot[dt][r] <-> channel 32 dt + (r/4)*8 + 4h + r%4
   float m;           // running max (log2 domain, scale included)
   float l;           // this lane's share of the row sum (keys with its h)
   float l_tail;      // this lane's share of the tail mass
 };
 
 // Per-lane constants of the staging layout, computed once per kernel.
-// LDS-DMA: wave w fills KB numbers w, w+4, w+8, w+12 of a staged 16 KB tile, i.e. tile rows
-// r0 + 16 i with r0 = 4 w + lane/16; rows 16 apart share their swizzle, so one per-lane
-// byte offset per format serves all four loads (the +4096 i goes into the scalar base).
+// LDS-DMA: wave w fills KB numbers w, w+4, ... of a staged tile (four per wave at D = 128, two
+// at D = 64); a KB is RPL rows, so load i covers tile rows r0 + 4 RPL i with r0 = RPL w +
+// lane / CPR.  Rows that far apart share their swizzle, so one per-lane byte offset per format
+// serves all loads (the +4096 i goes into the scalar base).
 struct LaneCtx {
   unsigned dma_k, dma_v;   // byte offset inside a global tile: K format / V format
   int dma_r0;              // tile row of the first load
@@ -175,14 +185,15 @@ struct LaneCtx {
 // completion is enforced by wait_async_loads() + barrier before a stage is read.
 // rows_avail < 64: rows past the end are replaced by the last valid row (finite data; such
 // keys are masked by the caller).
-template <bool KFMT>
+template <int D, bool KFMT>
 __device__ inline void load_tile_async(const LaneCtx& lc, const unsigned char* tile_base, int rows_avail,
                                        unsigned lds_stage /* LDS byte address of the destination tile */) {
   const unsigned voff = KFMT ? lc.dma_k : lc.dma_v;
   const unsigned m0_0 = __builtin_amdgcn_readfirstlane(lds_stage + lc.wave * 1024);
+  constexpr int NLD = Geo<D>::NLD, RPL = Geo<D>::RPL, ROWB = Geo<D>::ROWB;
   if (rows_avail >= kTile) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < NLD; ++i) {
       asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
                    :
                    : "s"(m0_0 + i * 4096), "v"(voff), "s"(tile_base + i * 4096)
@@ -190,8 +201,8 @@ __device__ inline void load_tile_async(const LaneCtx& lc, const unsigned char* t
     }
   } else {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int r = lc.dma_r0 + 16 * i;
+    for (int i = 0; i < NLD; ++i) {
+      const int r = lc.dma_r0 + 4 * RPL * i;
       const int back = max(r - (rows_avail - 1), 0);                    // rows to step back
       const unsigned char* src = tile_base + i * 4096 + (long long)voff - (long long)back * ROWB;
       asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
@@ -202,8 +213,8 @@ __device__ inline void load_tile_async(const LaneCtx& lc, const unsigned char* t
   }
 }
 
-// Load i (of four) of this wave's share of a FULL tile: the same instruction as in
-// load_tile_async, one at a time.
+// Load i of this wave's share of a FULL tile: the same instruction as in load_tile_async,
+// one at a time.
 template <bool KFMT>
 __device__ inline void load_tile_part(const LaneCtx& lc, const unsigned char* tile_base, unsigned lds_stage, int i) {
   const unsigned voff = KFMT ? lc.dma_k : lc.dma_v;
@@ -218,9 +229,18 @@ __device__ inline void load_tile_part(const LaneCtx& lc, const unsigned char* ti
 // four consecutive rows a 16-lane group reads together get 0,2,4,6 (or 1,3,5,7), so the two
 // groups of a half-wave (chunk indices differing in bit 0) hit disjoint banks: measured
 // 2.2 clk per ds_read_b64_tr_b16 against 4.2 clk with a plain (r & 7) XOR.
-__device__ inline int vswz(int r) { return ((r & 3) << 1) | ((r >> 2) & 1); }
+// At D = 64 a row has four 32-byte chunks and two rows share a bank line: rows 2m and 2m + 1
+// flip chunk bit 1 by m & 1, which again spreads the eight 32-byte pieces of a half-wave over
+// eight distinct bank groups.
+template <int D> __device__ inline int vswz(int r) {
+  return D == 128 ? (((r & 3) << 1) | ((r >> 2) & 1)) : (((r >> 1) & 1) << 1);
+}
+// K-format swizzle of the 16-byte chunk index: 16 rows of a ds_read_b128 pass must fall on 16
+// different bank groups (256-byte rows: row & 15; 128-byte rows pair up in a bank line:
+// (row >> 1) & 7).
+template <int D> __device__ inline int kswz(int r) { return D == 128 ? (r & 15) : ((r >> 1) & 7); }
 
-// The staging area is 1 KB aligned, so flipping address bits 5..7 stays inside a row.
+// The staging area is 1 KB aligned, so flipping address bits 4..6 (4..7 at D = 128) stays inside a row.
 __device__ inline LDS_PTR(const unsigned char) xor_ptr(LDS_PTR(const unsigned char) p, unsigned bits) {
   return (LDS_PTR(const unsigned char))(unsigned long long)((unsigned)(unsigned long long)p ^ bits);
 }
@@ -233,12 +253,13 @@ __device__ inline void wait_async_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); 
 // LaneCtx pointers refer to.
 
 // S^T = K_tile Q^T.
-template <int KOFF>
-__device__ inline void qk_tile(f32x16& s0, f32x16& s1, const bf16x8 (&qreg)[8], const LaneCtx& lc) {
+template <int D, int KOFF>
+__device__ inline void qk_tile(f32x16& s0, f32x16& s1, const bf16x8 (&qreg)[D / 16], const LaneCtx& lc) {
+  constexpr int ROWB = Geo<D>::ROWB;
   s0 = (f32x16){0};
   s1 = (f32x16){0};
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) {
+  for (int ks = 0; ks < D / 16; ++ks) {
     LDS_PTR(const unsigned char) kp = xor_ptr(lc.kbase, ks << 5);
     const bf16x8 a0 = *reinterpret_cast<LDS_PTR(const bf16x8)>(kp + KOFF);
     const bf16x8 a1 = *reinterpret_cast<LDS_PTR(const bf16x8)>(kp + KOFF + 32 * ROWB);
@@ -247,29 +268,31 @@ __device__ inline void qk_tile(f32x16& s0, f32x16& s1, const bf16x8 (&qreg)[8], 
   }
 }
 
-// qk_tile with the eight LDS-DMA loads of the next K / V tiles issued between its MFMAs, so
+// qk_tile with the LDS-DMA loads of the next K / V tiles issued between its MFMAs, so
 // that the issue cost of a load hides under a running MFMA.  K operands are read one step
 // ahead of their use (the loads order LDS reads around them).
-template <int KOFF>
-__device__ inline void qk_tile_dma(f32x16& s0, f32x16& s1, const bf16x8 (&qreg)[8], const LaneCtx& lc,
+template <int D, int KOFF>
+__device__ inline void qk_tile_dma(f32x16& s0, f32x16& s1, const bf16x8 (&qreg)[D / 16], const LaneCtx& lc,
                                    const unsigned char* kt, unsigned k_stage, const unsigned char* vt,
                                    unsigned v_stage) {
+  constexpr int ROWB = Geo<D>::ROWB, NKS = Geo<D>::NKS, NLD = Geo<D>::NLD;
+  static_assert(2 * NLD <= NKS, "the loads of both tiles must fit between the contraction steps");
   s0 = (f32x16){0};
   s1 = (f32x16){0};
   bf16x8 a0 = *reinterpret_cast<LDS_PTR(const bf16x8)>(lc.kbase + KOFF);
   bf16x8 a1 = *reinterpret_cast<LDS_PTR(const bf16x8)>(lc.kbase + KOFF + 32 * ROWB);
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) {
+  for (int ks = 0; ks < NKS; ++ks) {
     bf16x8 n0 = a0, n1 = a1;
-    if (ks < 7) {
+    if (ks < NKS - 1) {
       LDS_PTR(const unsigned char) kp = xor_ptr(lc.kbase, (ks + 1) << 5);
       n0 = *reinterpret_cast<LDS_PTR(const bf16x8)>(kp + KOFF);
       n1 = *reinterpret_cast<LDS_PTR(const bf16x8)>(kp + KOFF + 32 * ROWB);
     }
     s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qreg[ks], s0, 0, 0, 0);
     s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qreg[ks], s1, 0, 0, 0);
-    if (ks < 4) load_tile_part<true>(lc, kt, k_stage, ks);
-    else load_tile_part<false>(lc, vt, v_stage, ks - 4);
+    if (ks < NLD) load_tile_part<true>(lc, kt, k_stage, ks);
+    else if (ks < 2 * NLD) load_tile_part<false>(lc, vt, v_stage, ks - NLD);
     a0 = n0;
     a1 = n1;
   }
@@ -283,8 +306,8 @@ __device__ inline void qk_tile_dma(f32x16& s0, f32x16& s1, const bf16x8 (&qreg)[
 
 // Step 1: new running max; rescales l, l_tail and O if it moved.  Returns the (finite)
 // value to subtract.  TAIL: s0, s1 are turned into biased log2-domain logits in place.
-template <bool TAIL>
-__device__ inline float softmax_max(State& st, f32x16& s0, f32x16& s1, const LaneCtx& lc,
+template <int D, bool TAIL>
+__device__ inline float softmax_max(State<D>& st, f32x16& s0, f32x16& s1, const LaneCtx& lc,
                                     LDS_PTR(const float) bias, float c) {
   float tmax;
   if (TAIL) {
@@ -316,15 +339,15 @@ __device__ inline float softmax_max(State& st, f32x16& s0, f32x16& s1, const Lan
     st.l *= corr;
     st.l_tail *= corr;
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt) st.ot[dt] *= corr;
+    for (int dt = 0; dt < D / 32; ++dt) st.ot[dt] *= corr;
     st.m = m_new;
   }
   return m_safe;
 }
 
 // Step 2: probabilities, row-sum update, bf16 B operands pb[step] (16 keys each).
-template <bool TAIL, bool RAGGED>
-__device__ inline void softmax_exp(State& st, const f32x16& s0, const f32x16& s1, float m_safe,
+template <int D, bool TAIL, bool RAGGED>
+__device__ inline void softmax_exp(State<D>& st, const f32x16& s0, const f32x16& s1, float m_safe,
                                    bf16x8 (&pb)[4], const LaneCtx& lc, int nvalid, float c) {
   float x[32];
   const float nm = -m_safe;
@@ -364,7 +387,8 @@ __device__ inline void softmax_exp(State& st, const f32x16& s0, const f32x16& s1
 // far from the fp32 limit.  A wave that has absorbed nothing yet (max = -inf) gets +inf
 // everywhere and therefore always falls back on its first tile; NaN falls back as well.
 constexpr float kStaleLimit = 0x1p60f;
-__device__ inline float softmax_exp_stale(const State& st, const f32x16& s0, const f32x16& s1,
+template <int D>
+__device__ inline float softmax_exp_stale(const State<D>& st, const f32x16& s0, const f32x16& s1,
                                          bf16x8 (&pb)[4], float c) {
   const float nm = -st.m;
   float pa = 0.f, pc = 0.f;
@@ -388,12 +412,13 @@ __device__ inline float softmax_exp_stale(const State& st, const f32x16& s0, con
 // O^T += V^T P^T: four contraction steps of 16 keys.  Transposed LDS read: lane j of a
 // 16-lane group points at 4 channels of key (j >> 2) and receives channel (group base + j)
 // of the group's four keys.
-template <int VOFF>
-__device__ inline void pv_tile(State& st, const bf16x8 (&pb)[4], const LaneCtx& lc) {
+template <int D, int VOFF>
+__device__ inline void pv_tile(State<D>& st, const bf16x8 (&pb)[4], const LaneCtx& lc) {
+  constexpr int ROWB = Geo<D>::ROWB;
 #pragma unroll
   for (int step = 0; step < 4; ++step) {
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt) {
+    for (int dt = 0; dt < D / 32; ++dt) {
       LDS_PTR(unsigned char) vp =
           const_cast<LDS_PTR(unsigned char)>(xor_ptr(lc.vbase, dt << 6)) + VOFF + 16 * step * ROWB;
       const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<LDS_PTR(s16x4)>(vp));
@@ -407,23 +432,24 @@ __device__ inline void pv_tile(State& st, const bf16x8 (&pb)[4], const LaneCtx& 
 }
 
 // One staged tile, start to finish (ragged tile, centroid tiles).
-template <bool TAIL, bool RAGGED, int KOFF, int VOFF>
-__device__ inline void absorb_tile(State& st, const bf16x8 (&qreg)[8], const LaneCtx& lc,
+template <int D, bool TAIL, bool RAGGED, int KOFF, int VOFF>
+__device__ inline void absorb_tile(State<D>& st, const bf16x8 (&qreg)[D / 16], const LaneCtx& lc,
                                    LDS_PTR(const float) bias, int nvalid, float c) {
   f32x16 s0, s1;
   bf16x8 pb[4];
-  qk_tile<KOFF>(s0, s1, qreg, lc);
-  const float m_safe = softmax_max<TAIL>(st, s0, s1, lc, bias, c);
-  softmax_exp<TAIL, RAGGED>(st, s0, s1, m_safe, pb, lc, nvalid, c);
-  pv_tile<VOFF>(st, pb, lc);
+  qk_tile<D, KOFF>(s0, s1, qreg, lc);
+  const float m_safe = softmax_max<D, TAIL>(st, s0, s1, lc, bias, c);
+  softmax_exp<D, TAIL, RAGGED>(st, s0, s1, m_safe, pb, lc, nvalid, c);
+  pv_tile<D, VOFF>(st, pb, lc);
 }
 
 // LDS map of the staging area (byte offsets): K stages | V stages; Phase 2 reuses it as
 // centroid keys (K stage 0) and centroid values (V stage 0).
-constexpr int KST0 = 0, KST1 = TILEB, VST0 = 2 * TILEB, VST1 = 3 * TILEB;
-
-template <bool DENSE>
+template <int D, bool DENSE>
 __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
+  constexpr int ROWB = Geo<D>::ROWB, TILEB = Geo<D>::TILEB, NKS = Geo<D>::NKS, NDT = Geo<D>::NDT;
+  constexpr int CPR = Geo<D>::CPR, RPL = Geo<D>::RPL;
+  constexpr int KST0 = 0, KST1 = TILEB, VST0 = 2 * TILEB, VST1 = 3 * TILEB;
   __shared__ __attribute__((aligned(1024))) unsigned char stage[4 * TILEB];   // K0 | K1 | V0 | V1
   __shared__ unsigned int chosen[2][MASK_WORDS];
   __shared__ __attribute__((aligned(16))) float bias_s[2][kTile];
@@ -460,34 +486,34 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
   lc.h = h;
   lc.wave = __builtin_amdgcn_readfirstlane(wave);
   {
-    const int r = 4 * wave + (lane >> 4);        // tile row of this lane's first DMA load
-    const int pos = lane & 15;                   // 16-byte slot inside the LDS row
+    const int r = RPL * wave + lane / CPR;       // tile row of this lane's first DMA load
+    const int pos = lane % CPR;                  // 16-byte slot inside the LDS row
     lc.dma_r0 = r;
-    lc.dma_k = r * ROWB + ((pos ^ (r & 15)) << 4);
-    lc.dma_v = r * ROWB + (((((pos >> 1) ^ vswz(r)) << 1) | (pos & 1)) << 4);
+    lc.dma_k = r * ROWB + ((pos ^ kswz<D>(r)) << 4);
+    lc.dma_v = r * ROWB + (((((pos >> 1) ^ vswz<D>(r)) << 1) | (pos & 1)) << 4);
     const int j16 = lane & 15;
     const int kq = 4 * h + (j16 >> 2);           // key offset of this lane's V pointer (= key & 7)
     const int lhalf = (lane >> 4) & 1;
-    lc.kbase = lds + lam * ROWB + (((lam & 15) ^ h) << 4);
-    lc.vbase = lds + kq * ROWB + 8 * (j16 & 3) + ((lhalf ^ vswz(kq)) << 5);
+    lc.kbase = lds + lam * ROWB + ((kswz<D>(lam) ^ h) << 4);
+    lc.vbase = lds + kq * ROWB + 8 * (j16 & 3) + ((lhalf ^ vswz<D>(kq)) << 5);
   }
 
-  // ---- Q^T operand: this lane's query row, 8 channel slices of 16 ----
+  // ---- Q^T operand: this lane's query row, D/16 channel slices of 16 ----
   const int q_row = sg * QROWS + 32 * wave + lam;
-  bf16x8 qreg[8];
+  bf16x8 qreg[NKS];
   {
     const __bf16* qg = p.q + bh * (size_t)L * D;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
+    for (int ks = 0; ks < NKS; ++ks) {
       u32x4 w = {0, 0, 0, 0};
       if (q_row < L) w = *reinterpret_cast<const u32x4*>(qg + (size_t)q_row * D + 16 * ks + 8 * h);
       qreg[ks] = __builtin_bit_cast(bf16x8, w);
     }
   }
 
-  State st;
+  State<D> st;
 #pragma unroll
-  for (int dt = 0; dt < 4; ++dt) st.ot[dt] = (f32x16){0};
+  for (int dt = 0; dt < NDT; ++dt) st.ot[dt] = (f32x16){0};
   st.m = -INFINITY;
   st.l = 0.f;
   st.l_tail = 0.f;
@@ -555,10 +581,10 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
     return true;
   };
   auto issue_k = [&](int tile, int koff) {
-    load_tile_async<true>(lc, kg + (size_t)tile * TILEB, L - tile * kTile, lds_addr + koff);
+    load_tile_async<D, true>(lc, kg + (size_t)tile * TILEB, L - tile * kTile, lds_addr + koff);
   };
   auto issue_v = [&](int tile, int voff) {
-    load_tile_async<false>(lc, vg + (size_t)tile * TILEB, L - tile * kTile, lds_addr + voff);
+    load_tile_async<D, false>(lc, vg + (size_t)tile * TILEB, L - tile * kTile, lds_addr + voff);
   };
 
   // Software pipeline over tiles t = 0, 1, ...: K runs one tile ahead of V.  In trip t the
@@ -578,7 +604,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
     __syncthreads();
     if (have1) issue_k(t1, KST1);
     issue_v(t0, VST0);
-    if ((in0 >> qb) & 1) qk_tile<KST0>(sc0, sc1, qreg, lc);
+    if ((in0 >> qb) & 1) qk_tile<D, KST0>(sc0, sc1, qreg, lc);
   }
   auto trip = [&](auto parity_tag) {
     constexpr int P = decltype(parity_tag)::value;       // parity of the current tile
@@ -595,15 +621,15 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
       f32x16 sn0, sn1;
       bf16x8 pb[4];
       // straight-line: S^T(t+1) on the matrix cores, exp / sum / pack of tile t on the VALU
-      qk_tile_dma<K_NEXT>(sn0, sn1, qreg, lc, kg + (size_t)tk * TILEB, lds_addr + K_FREE,
+      qk_tile_dma<D, K_NEXT>(sn0, sn1, qreg, lc, kg + (size_t)tk * TILEB, lds_addr + K_FREE,
                           vg + (size_t)tv * TILEB, lds_addr + V_FREE);
       float psum = softmax_exp_stale(st, sc0, sc1, pb, c);
       if (__any(!(psum < kStaleLimit))) {          // first tile of this wave, or a maximum that ran away
-        softmax_max<false>(st, sc0, sc1, lc, nullptr, c);
+        softmax_max<D, false>(st, sc0, sc1, lc, nullptr, c);
         psum = softmax_exp_stale(st, sc0, sc1, pb, c);
       }
       st.l += psum;
-      pv_tile<V_CUR>(st, pb, lc);
+      pv_tile<D, V_CUR>(st, pb, lc);
       sc0 = sn0;
       sc1 = sn1;
     } else if (do_cur) {
@@ -612,15 +638,15 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
       bf16x8 pb[4];
       float psum = softmax_exp_stale(st, sc0, sc1, pb, c);
       if (__any(!(psum < kStaleLimit))) {
-        softmax_max<false>(st, sc0, sc1, lc, nullptr, c);
+        softmax_max<D, false>(st, sc0, sc1, lc, nullptr, c);
         psum = softmax_exp_stale(st, sc0, sc1, pb, c);
       }
       st.l += psum;
-      pv_tile<V_CUR>(st, pb, lc);
+      pv_tile<D, V_CUR>(st, pb, lc);
     } else {
       issue_k(tk, K_FREE);
       issue_v(tv, V_FREE);
-      if (do_next) qk_tile<K_NEXT>(sc0, sc1, qreg, lc);
+      if (do_next) qk_tile<D, K_NEXT>(sc0, sc1, qreg, lc);
     }
     t0 = t1; in0 = in1; have0 = have1;
     t1 = t2; in1 = in2; have1 = have2;
@@ -645,7 +671,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
       wait_async_loads();
       __syncthreads();
       if ((inm >> qb) & 1)
-        absorb_tile<false, true, KST0, VST0>(st, qreg, lc, nullptr, L - tile * kTile, c);
+        absorb_tile<D, false, true, KST0, VST0>(st, qreg, lc, nullptr, L - tile * kTile, c);
     }
   }
 
@@ -657,8 +683,8 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
     LDS_PTR(const float) my_bias = (LDS_PTR(const float)) & bias_s[qb][0];
     for (int g0 = 0; g0 < N; g0 += kTile) {
       __syncthreads();                         // previous tile fully consumed
-      load_tile_async<true>(lc, kcg + (size_t)g0 * ROWB, kTile, lds_addr + KST0);
-      load_tile_async<false>(lc, vbg + (size_t)g0 * ROWB, kTile, lds_addr + VST0);
+      load_tile_async<D, true>(lc, kcg + (size_t)g0 * ROWB, kTile, lds_addr + KST0);
+      load_tile_async<D, false>(lc, vbg + (size_t)g0 * ROWB, kTile, lds_addr + VST0);
       if (tid < 2 * kTile) {
         const int b = tid >> 6, j = g0 + (tid & 63);
         const bool masked =
@@ -667,7 +693,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
       }
       wait_async_loads();
       __syncthreads();
-      absorb_tile<true, false, KST0, VST0>(st, qreg, lc, my_bias, kTile, c);
+      absorb_tile<D, true, false, KST0, VST0>(st, qreg, lc, my_bias, kTile, c);
     }
   }
 
@@ -678,21 +704,21 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
   // ---- Phase 3: R^T = hsum^T (d_out x d_in) * Q^T (d_in x queries), weight l_tail / L * s ----
   if (approx && p.first_order) {
     const bf16x8* hp = reinterpret_cast<const bf16x8*>(p.hpack + bh * (size_t)(2 * D * D));
-    f32x16 rt[4];
+    f32x16 rt[NDT];
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt) rt[dt] = (f32x16){0};
+    for (int dt = 0; dt < NDT; ++dt) rt[dt] = (f32x16){0};
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks)
+    for (int ks = 0; ks < NKS; ++ks)
 #pragma unroll
-      for (int dt = 0; dt < 4; ++dt) {
-        const bf16x8 ahi = hp[(ks * 4 + dt) * 64 + lane];
-        const bf16x8 alo = hp[D * D / 8 + (ks * 4 + dt) * 64 + lane];
+      for (int dt = 0; dt < NDT; ++dt) {
+        const bf16x8 ahi = hp[(ks * NDT + dt) * 64 + lane];
+        const bf16x8 alo = hp[D * D / 8 + (ks * NDT + dt) * 64 + lane];
         rt[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ahi, qreg[ks], rt[dt], 0, 0, 0);
         rt[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(alo, qreg[ks], rt[dt], 0, 0, 0);
       }
     const float w = st.l_tail / (float)L * p.scale;
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt) st.ot[dt] += rt[dt] * w;
+    for (int dt = 0; dt < NDT; ++dt) st.ot[dt] += rt[dt] * w;
   }
 
   // ---- normalise and store: register group g of tile dt = channels 32 dt + 8 g + 4 h + 0..3 ----
@@ -700,7 +726,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
     const float inv_l = 1.f / st.l;
     __bf16* orow = p.out + (bh * (size_t)L + q_row) * D;
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
+    for (int dt = 0; dt < NDT; ++dt)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const u32x2 w = {pack_bf16(st.ot[dt][4 * g] * inv_l, st.ot[dt][4 * g + 1] * inv_l),
@@ -717,10 +743,12 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
 size_t attention_workspace_bytes(const Dims& dm) {
   if (dm.dtype != PISA_BF16) return 0;
   const size_t npad = (size_t)((dm.N + kTile - 1) / kTile) * kTile;
+  const size_t D = dm.d;
   return (size_t)dm.bh() * (2 * npad * D * 2 + 2 * D * D * 2) + npad * sizeof(float);
 }
 
-hipError_t launch_attention_bf16(const Dims& dm, const AttnArgs& a, hipStream_t stream) {
+template <int D>
+static hipError_t launch_attention_bf16_d(const Dims& dm, const AttnArgs& a, hipStream_t stream) {
   PB p{};
   p.q = (const __bf16*)a.q;
   p.k = (const __bf16*)a.k;
@@ -739,7 +767,7 @@ hipError_t launch_attention_bf16(const Dims& dm, const AttnArgs& a, hipStream_t 
   p.first_order = a.hsum != nullptr;
   const int grid = ((p.total + 63) / 64) * 64;
   if (a.dense) {
-    hipLaunchKernelGGL(attn_bf16_kernel<true>, dim3(grid), dim3(256), 0, stream, p);
+    hipLaunchKernelGGL((attn_bf16_kernel<D, true>), dim3(grid), dim3(256), 0, stream, p);
     return hipGetLastError();
   }
   if (a.k_top < dm.N && a.kbar) {
@@ -750,7 +778,7 @@ hipError_t launch_attention_bf16(const Dims& dm, const AttnArgs& a, hipStream_t 
     __bf16* vbar = kcen + tile_elems;
     __bf16* hpack = vbar + tile_elems;
     float* bias = reinterpret_cast<float*>(hpack + (size_t)dm.bh() * 2 * D * D);
-    hipLaunchKernelGGL(attn_prep_kernel, dim3(p.npad / kTile + kPackBlocks, dm.bh()), dim3(256), 0, stream,
+    hipLaunchKernelGGL(attn_prep_kernel<D>, dim3(p.npad / kTile + kPackBlocks, dm.bh()), dim3(256), 0, stream,
                        a.kbar, a.vsum, a.hsum, kcen, vbar, bias, hpack, dm.L, dm.B, dm.N, p.npad);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -759,8 +787,12 @@ hipError_t launch_attention_bf16(const Dims& dm, const AttnArgs& a, hipStream_t 
     p.hpack = hpack;
     p.bias = bias;
   }
-  hipLaunchKernelGGL(attn_bf16_kernel<false>, dim3(grid), dim3(256), 0, stream, p);
+  hipLaunchKernelGGL((attn_bf16_kernel<D, false>), dim3(grid), dim3(256), 0, stream, p);
   return hipGetLastError();
+}
+
+hipError_t launch_attention_bf16(const Dims& dm, const AttnArgs& a, hipStream_t stream) {
+  return dm.d == 64 ? launch_attention_bf16_d<64>(dm, a, stream) : launch_attention_bf16_d<128>(dm, a, stream);
 }
 
 }  // namespace pisa

@@ -361,7 +361,9 @@ hipError_t launch_block_heterogeneity(const Dims& dm, const void* k, const void*
       hipLaunchKernelGGL((frob_kernel<T, DD>), g3, dim3(256), 0, stream, (const T*)k, (const T*)v,      \
                          kbar64, hbar, log_m, dm.L, dm.B, dm.N, eps);                                   \
   } while (0)
-  if (dm.dtype == PISA_BF16)
+  if (dm.dtype == PISA_BF16 && dm.d == 64)
+    PISA_HET(__hip_bfloat16, 64);
+  else if (dm.dtype == PISA_BF16)
     PISA_HET(__hip_bfloat16, 128);
   else if (dm.d == 64)
     PISA_HET(float, 64);

@@ -64,7 +64,6 @@ FAKE = ctypes.c_void_p(0x1000)   # never dereferenced: validation fails first
     (dict(block=32), pisa.PISA_INVALID_ARG),
     (dict(head_dim=96), pisa.PISA_INVALID_ARG),
     (dict(dtype=7), pisa.PISA_INVALID_ARG),
-    (dict(dtype=pisa.PISA_BF16, head_dim=64), pisa.PISA_UNSUPPORTED),
     (dict(scale=float("nan")), pisa.PISA_INVALID_ARG),
 ])
 def test_bad_shapes_are_rejected(kw, code):

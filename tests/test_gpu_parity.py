@@ -134,6 +134,25 @@ def test_bf16_cases(lib, L, H, B, r):
     run_full_case(lib, w)
 
 
+@pytest.mark.parametrize("L,H,B,r", [
+    (1000, 3, 64, 0.8),
+    (2000, 2, 128, 0.85),
+    (1930, 2, 128, 0.6),
+    (70, 1, 64, 0.5),
+    (37, 1, 64, 0.0),
+    (640, 2, 64, 1.0),
+    (4200, 2, 64, 0.95),
+    (453, 2, 64, 0.5),
+    (9000, 2, 64, 0.85),         # long enough for many pipelined trips
+])
+def test_bf16_head_dim_64_cases(lib, L, H, B, r):
+    """The same ground as test_bf16_cases on the head_dim 64 build of the bf16 kernels (8 KB tiles,
+    128-byte rows, their own swizzles)."""
+    w = WORKLOADS["flux"].with_(name=f"bf16-d64-{L}", heads=H, seq_len=L, head_dim=64, block=B, sparsity=r,
+                                seed=40 + L, grid=None, block_offset_std=0.5)
+    run_full_case(lib, w)
+
+
 def test_bf16_zeroth_order_only(lib):
     """hsum = NULL drops the global first-order term (zeroth-order variant)."""
     w = WORKLOADS["flux"].with_(name="bf16-0th", heads=2, seq_len=1500, sparsity=0.8, grid=None,
@@ -141,7 +160,7 @@ def test_bf16_zeroth_order_only(lib):
     run_full_case(lib, w, first_order=False)
 
 
-@pytest.mark.parametrize("dtype,d,B", [("bf16", 128, 64), ("bf16", 128, 128), ("fp32", 64, 64)])
+@pytest.mark.parametrize("dtype,d,B", [("bf16", 128, 64), ("bf16", 128, 128), ("bf16", 64, 64), ("fp32", 64, 64)])
 def test_keep_or_drop_variant(lib, dtype, d, B):
     """kbar = vsum = NULL: block-sparse attention over S_i only (masked-softmax equation)."""
     w = WORKLOADS["tiny"].with_(name="sparse", heads=2, seq_len=1480, head_dim=d, dtype=dtype, block=B,
@@ -149,7 +168,7 @@ def test_keep_or_drop_variant(lib, dtype, d, B):
     run_full_case(lib, w, approximate=False)
 
 
-@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("fp32", 64)])
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("fp32", 64)])
 def test_batch_of_two(lib, dtype, d):
     """batch > 1: (batch, head) pairs are independent problems laid out back to back."""
     w = WORKLOADS["tiny"].with_(name="batch2", heads=2, seq_len=453, head_dim=d, dtype=dtype, sparsity=0.6, seed=41)
@@ -170,7 +189,8 @@ def test_batch_of_two(lib, dtype, d):
             assert rel <= TOL[q.dtype] and cos >= COS_MIN, (b, h, rel, cos)
 
 
-@pytest.mark.parametrize("dtype,d,B", [("bf16", 128, 64), ("bf16", 128, 128), ("fp32", 64, 64), ("fp32", 128, 128)])
+@pytest.mark.parametrize("dtype,d,B", [("bf16", 128, 64), ("bf16", 128, 128), ("bf16", 64, 64), ("bf16", 64, 128),
+                                       ("fp32", 64, 64), ("fp32", 128, 128)])
 def test_all_blocks_selected_is_bitwise_dense(lib, dtype, d, B):
     """At r = 0 the PISA kernel must return exactly what the dense kernel returns."""
     w = WORKLOADS["tiny"].with_(name="r0", heads=2, seq_len=1100, head_dim=d, dtype=dtype, block=B, sparsity=0.0)
@@ -183,7 +203,8 @@ def test_all_blocks_selected_is_bitwise_dense(lib, dtype, d, B):
     assert torch.equal(res["lse"], lse)
 
 
-@pytest.mark.parametrize("dtype,d,B,L", [("bf16", 128, 64, 1500), ("bf16", 128, 128, 1400), ("fp32", 64, 64, 900)])
+@pytest.mark.parametrize("dtype,d,B,L", [("bf16", 128, 64, 1500), ("bf16", 128, 128, 1400), ("bf16", 64, 64, 1300),
+                                         ("fp32", 64, 64, 900)])
 def test_covariance_aware_selection(lib, dtype, d, B, L):
     """Covariance-Aware Block Selection: log(M_j + eps) from pisa_block_heterogeneity (both
     norms) against the oracle's per-block H_j, then pisa_select with that column bias."""
