@@ -1,9 +1,10 @@
-// bf16 attention path (dense and PISA) on the gfx950 matrix cores, head_dim 128.
+// bf16 attention path (dense and PISA) on the gfx950 matrix cores, head_dim 128 or 64
+// (everything below is a template over the head dimension D).
 //
 // Workgroup = 4 wavefronts = 128 query rows (two adjacent 64-row query blocks, or one
 // 128-row block); wave w owns rows 32w..32w+31 and sees every key of a staged tile.
-// Two workgroups fit a CU (2 x 66 KB LDS, <= 256 VGPRs), so barrier stalls of one are
-// covered by the other.
+// Two workgroups fit a CU (2 x 66 KB LDS at D = 128, <= 256 VGPRs), so barrier stalls of one
+// are covered by the other.
 //
 // Everything is computed transposed with v_mfma_f32_32x32x16_bf16:
 //     S^T (keys x queries) = K_tile (keys x d)   *  Q^T (d x queries)
@@ -13,13 +14,19 @@
 // accumulator converts in place into the bf16 B operand of the second product (the key
 // order inside a contraction step is permuted identically on the V side).
 //
-// Staging: K and V tiles (64 rows x 256 B) go global -> LDS with global_load_lds_dwordx4
+// Staging: K and V tiles (64 rows x 2 D bytes) go global -> LDS with global_load_lds_dwordx4
 // (no registers in between), double buffered, one barrier per tile.  A wave-load writes
 // 1 KB of consecutive LDS, so bank conflicts are avoided by permuting which global chunk
-// each lane fetches: K rows XOR their 16-byte chunk index with (row & 15) (conflict-free
-// ds_read_b128 of one chunk from 16 different rows); V rows XOR their 32-byte chunk index
-// with a 3-bit function of the row (conflict-free ds_read_b64_tr_b16, which hands a 16-lane group a
+// each lane fetches: K rows XOR their 16-byte chunk index with a function of the row
+// (conflict-free ds_read_b128 of one chunk from 16 different rows); V rows XOR their 32-byte
+// chunk index with another (conflict-free ds_read_b64_tr_b16, which hands a 16-lane group a
 // 16-channel x 4-key transposed fragment, i.e. the V^T operand straight from row-major V).
+//
+// Tile loop: software-pipelined (K one tile ahead of V; S^T(t+1) issued in the same
+// straight-line block as the exponentials of tile t, with the next tiles' loads between its
+// MFMAs), and the running maximum is lazy: a full exact tile is exponentiated against the
+// maximum as it stands and the exact step (new maximum, rescale) runs only when a tile sum
+// nears overflow or on a wave's first tile.
 //
 // PISA, block 64: the two query blocks of a workgroup walk the UNION of their selected
 // key blocks in ascending order (bit scan over two LDS bitmasks); a tile selected by only
