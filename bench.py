@@ -108,8 +108,9 @@ def main():
                     help="file with {'fetch_bytes':..,'write_bytes':..} per attention launch from rocprofv3 --pmc")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the path shards over heads without "
-              "communication; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (the path shards over (batch, head) with no "
+              "communication, so N GPUs would each take their share of the heads); run with --gpus 1",
+              file=sys.stderr)
         sys.exit(2)
 
     import torch
