@@ -6,8 +6,6 @@
 // blocks of one head, keeps its share of H in registers, and writes one partial
 // d x d matrix; a second kernel adds the partials in chunk order, so hsum is
 // bit-identical from run to run.
-#include <hip/hip_bf16.h>
-
 #include "common.h"
 
 namespace pisa {
@@ -15,10 +13,8 @@ namespace {
 
 template <typename T> __device__ inline float to_f32(T x);
 template <> __device__ inline float to_f32<float>(float x) { return x; }
-template <> __device__ inline float to_f32<__hip_bfloat16>(__hip_bfloat16 x) { return __bfloat162float(x); }
 
-// Vector-ALU statistics kernel (the fp32 build, and bf16 at head_dim 64; bf16 at head_dim 128
-// takes the matrix-core kernel).
+// Vector-ALU statistics kernel (the fp32 build; bf16 inputs take the matrix-core kernel).
 //   LDS: kc[64][D] centred keys, vs[64][D] values, column-sum scratch.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void stats_kernel(
@@ -160,9 +156,7 @@ hipError_t launch_block_stats(const Dims& dm, const void* q, const void* k, cons
   hipLaunchKernelGGL((stats_kernel<T, DD>), grid, dim3(256), 0, stream, (const T*)q, (const T*)k, \
                      (const T*)v, qbar, kbar, vsum, qbar64, kbar64, partial_h, dm.L, dm.B, dm.N,   \
                      plan.chunk_blocks, plan.n_chunks)
-  if (dm.dtype == PISA_BF16 && dm.d == 64) {
-    PISA_STATS(__hip_bfloat16, 64);
-  } else if (dm.dtype == PISA_BF16) {
+  if (dm.dtype == PISA_BF16) {
     hipError_t e = launch_block_stats_bf16(dm, q, k, v, qbar, kbar, vsum, qbar64, kbar64,
                                            partial_h, plan, stream);
     if (e != hipSuccess) return e;

@@ -1,4 +1,5 @@
-// pisa_block_stats for bf16 inputs, head_dim 128, block 64 or 128: one streaming pass (Alg. 1 line 1).
+// pisa_block_stats for bf16 inputs, head_dim 128 or 64, block 64 or 128: one streaming pass
+// (Alg. 1 line 1).  Written out for head_dim 128; the differences at 64 are noted where they occur.
 //
 // Grid (n_chunks, batch*heads); a workgroup of 4 waves walks `chunk_blocks` consecutive
 // blocks of one head.  Per 64-token (sub-)block:
@@ -28,9 +29,6 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef double f64x2 __attribute__((ext_vector_type(2)));
 #define LDS_PTR(T) __attribute__((address_space(3))) T*
 
-constexpr int D = 128;
-constexpr int ROWB = 256;
-constexpr int TILEB = kTile * ROWB;
 
 __device__ inline unsigned int pack_bf16(float lo, float hi) {
   f32x2 f = {lo, hi};
@@ -39,21 +37,26 @@ __device__ inline unsigned int pack_bf16(float lo, float hi) {
 }
 
 // Swizzle of a staged [token][channel] tile: the 32-byte chunk index of row n is XORed with
-// this 3-bit value, which makes the transposed reads below bank-conflict free.
-__device__ inline int swz3(int n) { return ((n & 3) << 1) | ((n >> 2) & 1); }
+// this value, which makes the transposed reads below bank-conflict free (256-byte rows: a
+// 3-bit pattern; 128-byte rows, two to a bank line: bit 1 flipped for every other row pair).
+template <int D> __device__ inline int swz3(int n) {
+  return D == 128 ? (((n & 3) << 1) | ((n >> 2) & 1)) : (((n >> 1) & 1) << 1);
+}
 
 // Byte address of channel pair `c2` (channels 2 c2, 2 c2 + 1) of row n in a swizzled tile.
-__device__ inline int swz_pair(int n, int c2) {
+template <int D> __device__ inline int swz_pair(int n, int c2) {
   const int byte = c2 * 4;
-  return n * ROWB + ((((byte >> 5) ^ swz3(n)) << 5) | (byte & 31));
+  return n * (2 * D) + ((((byte >> 5) ^ swz3<D>(n)) << 5) | (byte & 31));
 }
 
 // A / B operand of v_mfma_f32_32x32x16_bf16 for contraction step `step` (16 tokens) and
 // channel tile `ct` (32 channels), read transposed from a swizzled [token][channel] tile.
+template <int D>
 __device__ inline bf16x8 read_operand(LDS_PTR(const unsigned char) tile, int lane, int step, int ct) {
+  constexpr int ROWB = 2 * D;
   const int j16 = lane & 15, h = lane >> 5, lhalf = (lane >> 4) & 1;
   const int kq = 4 * h + (j16 >> 2);
-  const int off = (16 * step + kq) * ROWB + 8 * (j16 & 3) + (((2 * ct + lhalf) ^ swz3(kq)) << 5);
+  const int off = (16 * step + kq) * ROWB + 8 * (j16 & 3) + (((2 * ct + lhalf) ^ swz3<D>(kq)) << 5);
   LDS_PTR(unsigned char) p = const_cast<LDS_PTR(unsigned char)>(tile) + off;
   const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<LDS_PTR(s16x4)>(p));
   const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<LDS_PTR(s16x4)>(p + 8 * ROWB));
@@ -67,13 +70,21 @@ __device__ inline bf16x8 read_operand(LDS_PTR(const unsigned char) tile, int lan
 // block's H_j follows from  sum_n (k_n - c_s)^T v_n = sum_n (k_n - kbar_j)^T v_n + (kbar_j - c_s)^T Vhat_s :
 //   H_j = sum_s [ A_s + (c_s - kbar_j)^T Vhat_s ],
 // a small rank-one correction per sub-block (c_s is close to kbar_j, so nothing cancels).
-template <int TPB>
+// Head_dim 64: a 256-byte wave-load is two rows (lane = row parity x channel pair), a lane
+// holds 8 rows per tensor instead of 16, the two row parities are added with one lane
+// exchange, and the 64 x 64 matrix H is four 32 x 32 tiles, one per wave.
+template <int D, int TPB>
 __global__ __launch_bounds__(256, 2) void stats_bf16_kernel(
     const unsigned int* __restrict__ q, const unsigned int* __restrict__ k, const unsigned int* __restrict__ v,
     float* __restrict__ qbar, float* __restrict__ kbar, float* __restrict__ vsum,
     double* __restrict__ qbar64, double* __restrict__ kbar64, float* __restrict__ partial_h,
     int L, int N, int chunk_blocks, int n_chunks) {
   constexpr int B = TPB * kTile;
+  constexpr int TILEB = kTile * 2 * D;
+  constexpr int LPR = D / 2;            // lanes per row (one channel pair each)
+  constexpr int RPW = 64 / LPR;         // rows per wave-load
+  constexpr int NR = 16 / RPW;          // loads per lane and tensor
+  constexpr int NB = D / 32 / (D == 128 ? 1 : 2);   // value tiles per wave: 4, or 1
   __shared__ __attribute__((aligned(1024))) unsigned char khi_s[TILEB];
   __shared__ __attribute__((aligned(1024))) unsigned char klo_s[TILEB];
   __shared__ __attribute__((aligned(1024))) unsigned char v_s[TILEB];
@@ -96,17 +107,21 @@ __global__ __launch_bounds__(256, 2) void stats_bf16_kernel(
   LDS_PTR(unsigned char) klo = (LDS_PTR(unsigned char))klo_s;
   LDS_PTR(unsigned char) vt = (LDS_PTR(unsigned char))v_s;
   const int lam = lane & 31, h = lane >> 5;
+  const int rp = lane / LPR, cp = lane % LPR;        // row parity inside a wave-load, channel pair
+  const int ktile = D == 128 ? wave : (wave & 1);    // this wave's 32 key channels of H
+  const int vtile0 = D == 128 ? 0 : (wave >> 1);     // its first 32-value-channel tile
 
-  f32x16 acc[4];
+  f32x16 acc[NB];
 #pragma unroll
-  for (int bt = 0; bt < 4; ++bt) acc[bt] = (f32x16){0};
+  for (int bt = 0; bt < NB; ++bt) acc[bt] = (f32x16){0};
 
   // This wave's 16 rows of one 64-token sub-block, one channel pair per lane.  Rows past the
   // end repeat the last valid row (the users mask them), so the loads carry no conditions.
-  auto load_rows = [&](const unsigned int* src, int row0, int rows, unsigned int (&x)[16]) {
+  auto load_rows = [&](const unsigned int* src, int row0, int rows, unsigned int (&x)[NR]) {
     if (rows <= 0) return;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) x[i] = src[(size_t)(row0 + min(16 * wave + i, rows - 1)) * (D / 2) + lane];
+    for (int i = 0; i < NR; ++i)
+      x[i] = src[(size_t)(row0 + min(16 * wave + RPW * i + rp, rows - 1)) * (D / 2) + cp];
   };
 
   const int j_begin = chunk * chunk_blocks;
@@ -114,7 +129,7 @@ __global__ __launch_bounds__(256, 2) void stats_bf16_kernel(
   // The rows of sub-block t + 1 are requested while sub-block t is worked on (K and V at its
   // start into a second register set, Q into its own registers once its sums are taken), so a
   // wave always has 8 to 12 KB of loads in flight.
-  unsigned int kx[16] = {}, vx[16] = {}, qx[16] = {}, kn[16] = {}, vn[16] = {};
+  unsigned int kx[NR] = {}, vx[NR] = {}, qx[NR] = {}, kn[NR] = {}, vn[NR] = {};
   if (j_begin < j_end) {
     const int rows = min(kTile, L - j_begin * B);
     load_rows(qh, j_begin * B, rows, qx);
@@ -144,8 +159,8 @@ __global__ __launch_bounds__(256, 2) void stats_bf16_kernel(
       // ---- fp64 column sums of the 16 rows (absent rows are zeroed first) ----
       double sq0 = 0, sq1 = 0, sk0 = 0, sk1 = 0, sv0 = 0, sv1 = 0;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        if (16 * wave + i >= rows) {              // uniform
+      for (int i = 0; i < NR; ++i) {
+        if (16 * wave + RPW * i + rp >= rows) {   // uniform at head_dim 128
           qx[i] = kx[i] = vx[i] = 0u;
         }
         sq0 += (double)__uint_as_float(qx[i] << 16);
@@ -155,9 +170,16 @@ __global__ __launch_bounds__(256, 2) void stats_bf16_kernel(
         sv0 += (double)__uint_as_float(vx[i] << 16);
         sv1 += (double)__uint_as_float(vx[i] & 0xffff0000u);
       }
-      *reinterpret_cast<f64x2*>(&red[0][wave][2 * lane]) = (f64x2){sq0, sq1};
-      *reinterpret_cast<f64x2*>(&red[1][wave][2 * lane]) = (f64x2){sk0, sk1};
-      *reinterpret_cast<f64x2*>(&red[2][wave][2 * lane]) = (f64x2){sv0, sv1};
+      if (RPW == 2) {                             // the other row parity of the same channels
+        sq0 += __shfl_xor(sq0, 32); sq1 += __shfl_xor(sq1, 32);
+        sk0 += __shfl_xor(sk0, 32); sk1 += __shfl_xor(sk1, 32);
+        sv0 += __shfl_xor(sv0, 32); sv1 += __shfl_xor(sv1, 32);
+      }
+      if (lane < LPR) {
+        *reinterpret_cast<f64x2*>(&red[0][wave][2 * cp]) = (f64x2){sq0, sq1};
+        *reinterpret_cast<f64x2*>(&red[1][wave][2 * cp]) = (f64x2){sk0, sk1};
+        *reinterpret_cast<f64x2*>(&red[2][wave][2 * cp]) = (f64x2){sv0, sv1};
+      }
       load_rows(qh, next_row0, next_rows, qx);    // Q(t) is used up
       __syncthreads();
       if (tid < D) {
@@ -185,10 +207,10 @@ __global__ __launch_bounds__(256, 2) void stats_bf16_kernel(
       __syncthreads();
       // ---- centre K on the sub-block mean, split hi/lo, stage with V ----
       {
-        const float m0 = kmean_s[2 * lane], m1 = kmean_s[2 * lane + 1];
+        const float m0 = kmean_s[2 * cp], m1 = kmean_s[2 * cp + 1];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int n = 16 * wave + i;
+        for (int i = 0; i < NR; ++i) {
+          const int n = 16 * wave + RPW * i + rp;
           unsigned int hi = 0u, lo = 0u;
           if (n < rows) {
             const float c0 = __uint_as_float(kx[i] << 16) - m0;
@@ -196,28 +218,28 @@ __global__ __launch_bounds__(256, 2) void stats_bf16_kernel(
             hi = pack_bf16(c0, c1);
             lo = pack_bf16(c0 - __uint_as_float(hi << 16), c1 - __uint_as_float(hi & 0xffff0000u));
           }
-          const int a = swz_pair(n, lane);
+          const int a = swz_pair<D>(n, cp);
           *reinterpret_cast<LDS_PTR(unsigned int)>(khi + a) = hi;
           *reinterpret_cast<LDS_PTR(unsigned int)>(klo + a) = lo;
           *reinterpret_cast<LDS_PTR(unsigned int)>(vt + a) = vx[i];
         }
       }
       __syncthreads();
-      // ---- H[32 wave .. +32][all 128] += Kc^T V over the 64 tokens ----
+      // ---- H[32 ktile .. +32][this wave's value tiles] += Kc^T V over the 64 tokens ----
 #pragma unroll
       for (int step = 0; step < 4; ++step) {
-        const bf16x8 ahi = read_operand(khi, lane, step, wave);
-        const bf16x8 alo = read_operand(klo, lane, step, wave);
+        const bf16x8 ahi = read_operand<D>(khi, lane, step, ktile);
+        const bf16x8 alo = read_operand<D>(klo, lane, step, ktile);
 #pragma unroll
-        for (int bt = 0; bt < 4; ++bt) {
-          const bf16x8 b = read_operand(vt, lane, step, bt);
+        for (int bt = 0; bt < NB; ++bt) {
+          const bf16x8 b = read_operand<D>(vt, lane, step, vtile0 + bt);
           acc[bt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ahi, b, acc[bt], 0, 0, 0);
           acc[bt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(alo, b, acc[bt], 0, 0, 0);
         }
       }
       // the next sub-block's LDS writes are separated from these reads by its two barriers
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
+      for (int i = 0; i < NR; ++i) {
         kx[i] = kn[i];
         vx[i] = vn[i];
       }
@@ -237,23 +259,23 @@ __global__ __launch_bounds__(256, 2) void stats_bf16_kernel(
       __syncthreads();
       for (int sub = 0; sub < n_sub; ++sub) {
 #pragma unroll
-        for (int bt = 0; bt < 4; ++bt) {
-          const float vb = vsub[sub][32 * bt + lam];
+        for (int bt = 0; bt < NB; ++bt) {
+          const float vb = vsub[sub][32 * (vtile0 + bt) + lam];
 #pragma unroll
           for (int r = 0; r < 16; ++r)
-            acc[bt][r] = fmaf(dks[sub][32 * wave + (r / 4) * 8 + 4 * h + (r % 4)], vb, acc[bt][r]);
+            acc[bt][r] = fmaf(dks[sub][32 * ktile + (r / 4) * 8 + 4 * h + (r % 4)], vb, acc[bt][r]);
         }
       }
       __syncthreads();                            // dks / vsub / tot are rewritten by the next block
     }
   }
-  // acc[bt][r] = H[32 wave + (r/4)*8 + 4h + r%4][32 bt + lam]
+  // acc[bt][r] = H[32 ktile + (r/4)*8 + 4h + r%4][32 (vtile0 + bt) + lam]
   float* ph = partial_h + (bh * n_chunks + chunk) * (size_t)D * D;
 #pragma unroll
-  for (int bt = 0; bt < 4; ++bt)
+  for (int bt = 0; bt < NB; ++bt)
 #pragma unroll
     for (int r = 0; r < 16; ++r)
-      ph[(size_t)(32 * wave + (r / 4) * 8 + 4 * h + (r % 4)) * D + 32 * bt + lam] = acc[bt][r];
+      ph[(size_t)(32 * ktile + (r / 4) * 8 + 4 * h + (r % 4)) * D + 32 * (vtile0 + bt) + lam] = acc[bt][r];
 }
 
 }  // namespace
@@ -263,14 +285,15 @@ hipError_t launch_block_stats_bf16(const Dims& dm, const void* q, const void* k,
                                    double* qbar64, double* kbar64, float* partial_h,
                                    const StatsPlan& plan, hipStream_t stream) {
   const dim3 grid(plan.n_chunks, dm.bh());
-  if (dm.B == kTile)
-    hipLaunchKernelGGL(stats_bf16_kernel<1>, grid, dim3(256), 0, stream, (const unsigned int*)q,
-                       (const unsigned int*)k, (const unsigned int*)v, qbar, kbar, vsum, qbar64, kbar64,
-                       partial_h, dm.L, dm.N, plan.chunk_blocks, plan.n_chunks);
-  else
-    hipLaunchKernelGGL(stats_bf16_kernel<2>, grid, dim3(256), 0, stream, (const unsigned int*)q,
-                       (const unsigned int*)k, (const unsigned int*)v, qbar, kbar, vsum, qbar64, kbar64,
-                       partial_h, dm.L, dm.N, plan.chunk_blocks, plan.n_chunks);
+#define PISA_STATS_BF16(DD, TPB)                                                                           \
+  hipLaunchKernelGGL((stats_bf16_kernel<DD, TPB>), grid, dim3(256), 0, stream, (const unsigned int*)q,     \
+                     (const unsigned int*)k, (const unsigned int*)v, qbar, kbar, vsum, qbar64, kbar64,     \
+                     partial_h, dm.L, dm.N, plan.chunk_blocks, plan.n_chunks)
+  if (dm.d == 128 && dm.B == kTile) PISA_STATS_BF16(128, 1);
+  else if (dm.d == 128) PISA_STATS_BF16(128, 2);
+  else if (dm.B == kTile) PISA_STATS_BF16(64, 1);
+  else PISA_STATS_BF16(64, 2);
+#undef PISA_STATS_BF16
   return hipGetLastError();
 }
 
