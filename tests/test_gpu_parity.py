@@ -153,6 +153,29 @@ def test_bf16_head_dim_64_cases(lib, L, H, B, r):
     run_full_case(lib, w)
 
 
+def _random_case(i):
+    rng = np.random.default_rng(1000 + i)
+    dtype, d = [("bf16", 128), ("bf16", 64), ("fp32", 64), ("fp32", 128)][i % 4]
+    B = int(rng.choice([64, 128]))
+    L = int(rng.choice([rng.integers(1, 130), rng.integers(130, 700), rng.integers(700, 1500),
+                        64 * rng.integers(1, 20), 128 * rng.integers(1, 10) + 1]))
+    r = float(rng.choice([0.0, 1.0, rng.uniform(0.0, 1.0), rng.uniform(0.5, 0.98)]))
+    mode = ["hybrid", "hybrid", "zeroth", "sparse"][int(rng.integers(0, 4))]
+    return dtype, d, B, L, r, mode, int(rng.integers(1, 4))
+
+
+@pytest.mark.parametrize("i", range(32))
+def test_random_small_shapes(lib, i):
+    """Seeded random small problems over every build (bf16 / fp32, head_dim 64 / 128, block 64 /
+    128), lengths on and around tile and block boundaries, any sparsity, all three variants."""
+    dtype, d, B, L, r, mode, H = _random_case(i)
+    w = WORKLOADS["flux"].with_(name=f"rand{i}-{dtype}-d{d}-{mode}", heads=H, seq_len=L, head_dim=d, dtype=dtype,
+                                block=B, sparsity=r, seed=500 + i, grid=None, block_offset_std=0.5)
+    if mode == "sparse" and w.topk == 0:
+        mode = "hybrid"                  # keep-or-drop needs at least one block
+    run_full_case(lib, w, first_order=(mode == "hybrid"), approximate=(mode != "sparse"))
+
+
 def test_bf16_zeroth_order_only(lib):
     """hsum = NULL drops the global first-order term (zeroth-order variant)."""
     w = WORKLOADS["flux"].with_(name="bf16-0th", heads=2, seq_len=1500, sparsity=0.8, grid=None,
