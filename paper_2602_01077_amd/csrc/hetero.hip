@@ -10,7 +10,8 @@
 //   (2) frob_kernel     one workgroup per block rebuilds H_j the same way, subtracts Hbar and
 //                       takes the Frobenius norm; or
 //       hetero_kernel   (spectral norm) rebuilds H_j on the vector ALUs, a thread owning an
-//                       R x R patch (R = d/16), and runs a power iteration on D^T D.
+//                       R x R patch (R = d/16), and runs a power iteration on D^T D (at most
+//                       the given number of steps, fewer once the estimate stands still).
 #include <hip/hip_bf16.h>
 
 #include "common.h"
@@ -291,6 +292,7 @@ __global__ __launch_bounds__(256) void hetero_kernel(const T* __restrict__ k, co
       const double n2 = sum_first_threads<D>(tid < D ? xs[tid] * xs[tid] : 0.0, red);
       if (tid < D) xs[tid] /= sqrt(n2);
     }
+    double ev_prev = 0.0;
     for (int it = 0; it <= n_iter; ++it) {
       __syncthreads();
       // y = D x
@@ -329,6 +331,11 @@ __global__ __launch_bounds__(256) void hetero_kernel(const T* __restrict__ k, co
       }
       const double n2 = sum_first_threads<D>(zv * zv, red);
       if (tid < D) xs[tid] = n2 > 0.0 ? zv / sqrt(n2) : xs[tid];
+      // ||D^T D x|| with ||x|| = 1 rises towards the largest eigenvalue: once it has stopped
+      // moving (relative step below 1e-4, uniform over the workgroup) the next pass is the last.
+      const double ev = sqrt(n2);
+      if (it >= 3 && it < n_iter - 1 && fabs(ev - ev_prev) <= 1e-4 * ev) it = n_iter - 1;
+      ev_prev = ev;
     }
   }
   if (tid == 0) log_m[bh * N + j] = log(m_norm + eps);
