@@ -21,7 +21,7 @@
  *     Blocks are consecutive runs of `block` tokens; N = ceil(seq_len / block); the last
  *     block may be ragged (B_j < block rows) -- statistics run over its valid rows.
  *   - Supported: dtype PISA_BF16 with head_dim 128 or 64 (MFMA path); dtype PISA_FP32 with
- *     head_dim 64 or 128 (fp32 path); block 64 or 128.
+ *     head_dim 64 or 128 (fp32 path); block 64 or 128; batch * heads <= 65535.
  *   - Every function returns a status code; pisa_last_error() gives the message of the
  *     last failure on the calling thread.  Arguments are validated before any device
  *     call, so argument errors are reported on a host without a GPU as well.

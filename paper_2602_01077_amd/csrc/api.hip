@@ -40,6 +40,8 @@ static int32_t resolve(const pisa_shape* s, Dims* dm) {
     return fail(PISA_INVALID_ARG, "head_dim must be 64 or 128, got %d", s->head_dim);
   if (!(s->scale == s->scale) || std::isinf(s->scale))
     return fail(PISA_INVALID_ARG, "scale is not finite");
+  if ((long long)s->batch * s->heads > 65535)     // several kernels put batch * heads on a 16-bit grid axis
+    return fail(PISA_UNSUPPORTED, "batch * heads = %lld exceeds 65535", (long long)s->batch * s->heads);
   long long rows = (long long)s->batch * s->heads * s->seq_len;
   if (rows * s->head_dim >= (1LL << 40))
     return fail(PISA_UNSUPPORTED, "tensor too large");

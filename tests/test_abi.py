@@ -65,6 +65,7 @@ FAKE = ctypes.c_void_p(0x1000)   # never dereferenced: validation fails first
     (dict(head_dim=96), pisa.PISA_INVALID_ARG),
     (dict(dtype=7), pisa.PISA_INVALID_ARG),
     (dict(scale=float("nan")), pisa.PISA_INVALID_ARG),
+    (dict(batch=300, heads=300), pisa.PISA_UNSUPPORTED),
 ])
 def test_bad_shapes_are_rejected(kw, code):
     lib = pisa.raw()
