@@ -237,15 +237,16 @@ def main():
     # HBM-side traffic of the attention kernel per launch comes from separate rocprofv3 --pmc
     # runs (counters cannot be read from inside this process); the committed summary applies
     # to the default workload only.
-    traffic = None
+    traffic = traffic_detail = None
     tj = args.traffic_json
     if tj is None and args.workload == "wan" and args.sparsity is None and args.block is None:
         tj = os.path.join(ROOT, "profiles", "wan_r085_traffic.txt")
     if tj and os.path.exists(tj):
         with open(tj) as f:
             t = json.load(f)
-        traffic = {"fetch_bytes": t["fetch_bytes"], "write_bytes": t["write_bytes"],
-                   "algorithmic_bytes": t.get("algorithmic_bytes"), "source": t.get("source")}
+        traffic = t["fetch_bytes"] + t["write_bytes"]        # bytes per launch past the L2
+        traffic_detail = {"fetch_bytes": t["fetch_bytes"], "write_bytes": t["write_bytes"],
+                          "algorithmic_bytes": t.get("algorithmic_bytes"), "source": t.get("source")}
     in_bytes = 3 * q.numel() * q.element_size()
     result = {
         "metric": "PISA attn ms/call & MFMA util at Wan2.1 shape, r=0.85; speedup vs dense",
@@ -269,7 +270,8 @@ def main():
         "l1_error_vs_dense": None if l1_vs_dense is None else round(l1_vs_dense, 6),
         "roofline": {"kernel": "attn_bf16_kernel (pisa_attention)", "bound": "mfma",
                      "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": traffic},
+                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
+                     "traffic_unit": "bytes per launch", "traffic_detail": traffic_detail},
         "measured_peaks": measured,
     }
     if measured:
