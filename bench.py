@@ -80,8 +80,8 @@ def cpu_baseline(w, q, k, v, scale, k_top, budget_s=15.0):
     return {
         "value": round(total_ms, 1), "unit": "ms/call", "cores": int(cores), "kind": "oracle",
         "sample": (f"{n_heads} of {w.heads} heads: full block statistics ({t_stats:.2f} s) and selection "
-                   f"({t_select:.2f} s); attention rows of {n_blocks} query blocks of {N} per head "
-                   f"({t_attn:.2f} s); extrapolated to all query blocks and heads"),
+                   f"({t_select:.2f} s); attention rows of {n_blocks} query blocks over those heads "
+                   f"({N} per head; {t_attn:.2f} s); extrapolated to all query blocks and heads"),
     }
 
 
