@@ -1,7 +1,7 @@
 // pisa_select: pooled block logits and top-k per query block (Alg. 1 line 2), with the
 // optional log(M_j + eps) column bias of the covariance-aware score.
 //
-// Two kernels.  (1) fp64 logits z[bh][i][j] = s * qbar_i . kbar_j on the fp64 matrix
+// Two kernels (one fused kernel when N <= 128).  (1) fp64 logits z[bh][i][j] = s * qbar_i . kbar_j on the fp64 matrix
 // cores, one wave per 64x64 tile, written to scratch.  (2) One WAVE per row, the row's
 // order-preserving 64-bit keys in registers: a bucket select narrows a key interval around
 // the k-th largest logit (256 buckets per level over the tightened [min, max] of the
@@ -171,25 +171,17 @@ __device__ inline int lanes_below(unsigned long long mask) {   // set bits of ma
   return __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0u));
 }
 
-// One wave per (bh, query block i), four rows per workgroup.  Lane l holds keys l, l + 64, ...
-// in registers (KPL of them, so N <= 64 * KPL); LDS holds only the wave's 256-bin histogram.
+// Top-k of one row by one wave.  Lane l holds keys l, l + 64, ... in registers (KPL of them,
+// so N <= 64 * KPL); `hist` is the wave's own 256-bin histogram in LDS; `zr` may point into
+// global memory or LDS; `gap` (optional) is this row's kth_gap slot.
 template <int KPL>
-__global__ __launch_bounds__(256) void topk_kernel(const double* __restrict__ z, int N, int k_top,
-                                                   size_t n_rows, int32_t* __restrict__ idx,
-                                                   float* __restrict__ kth_gap) {
-  __shared__ int hist_all[4][256];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const size_t row = (size_t)blockIdx.x * 4 + wave;
-  if (row >= n_rows) return;               // whole wave; the kernel has no workgroup barriers
-  int* hist = hist_all[wave];
-  int32_t* out = idx + row * (size_t)k_top;
-
+__device__ inline void topk_row(const double* zr, int N, int k_top, int* hist, int32_t* __restrict__ out,
+                                float* __restrict__ gap, int lane) {
   if (k_top == 0 || k_top == N) {
     for (int j = lane; j < k_top; j += 64) out[j] = j;
-    if (kth_gap && lane == 0) kth_gap[row] = __int_as_float(0x7f800000);
+    if (gap && lane == 0) *gap = __int_as_float(0x7f800000);
     return;
   }
-  const double* zr = z + row * (size_t)N;
   unsigned long long key[KPL];
 #pragma unroll
   for (int u = 0; u < KPL; ++u) key[u] = order_key(zr[min(lane + 64 * u, N - 1)]);
@@ -294,11 +286,75 @@ __global__ __launch_bounds__(256) void topk_kernel(const double* __restrict__ z,
     base += __builtin_popcountll(sel_mask);
     eq_seen += __builtin_popcountll(eq_mask);
   }
-  if (kth_gap) {
+  if (gap) {
     min_sel = wave_min_u64(min_sel);
     max_unsel = wave_max_u64(max_unsel);
-    if (lane == 0) kth_gap[row] = (float)(key_value(min_sel) - key_value(max_unsel));
+    if (lane == 0) *gap = (float)(key_value(min_sel) - key_value(max_unsel));
   }
+}
+
+// One wave per (bh, query block i), four rows per workgroup.
+template <int KPL>
+__global__ __launch_bounds__(256) void topk_kernel(const double* __restrict__ z, int N, int k_top,
+                                                   size_t n_rows, int32_t* __restrict__ idx,
+                                                   float* __restrict__ kth_gap) {
+  __shared__ int hist_all[4][256];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const size_t row = (size_t)blockIdx.x * 4 + wave;
+  if (row >= n_rows) return;               // whole wave; the kernel has no workgroup barriers
+  topk_row<KPL>(z + row * (size_t)N, N, k_top, hist_all[wave], idx + row * (size_t)k_top,
+                kth_gap ? kth_gap + row : nullptr, lane);
+}
+
+// Logits and top-k in one launch for N <= 128 (sequences of a few thousand tokens, where a
+// launch costs as much as either kernel).  A workgroup of 16 waves takes 16 query blocks of
+// one head: waves 0 .. ceil(N/16)-1 each compute one 16x16 logits tile exactly as
+// logits_small_kernel does and park it in LDS, then every wave selects one row.
+constexpr int kFusedMaxN = 128;
+template <int D>
+__global__ __launch_bounds__(1024) void select_small_kernel(const double* __restrict__ qbar64,
+                                                            const double* __restrict__ kbar64,
+                                                            const double* __restrict__ col_bias, int N,
+                                                            double scale, int k_top,
+                                                            int32_t* __restrict__ idx,
+                                                            float* __restrict__ kth_gap) {
+  __shared__ double zs[16][kFusedMaxN];
+  __shared__ int hist_all[16][256];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const size_t bh = blockIdx.y;
+  const int i0 = blockIdx.x * 16;
+  const int j0 = wave * 16;
+  if (j0 < N) {                            // wave-uniform
+    const int r = lane & 15, kk = lane >> 4;
+    const double* qp = qbar64 + (bh * N + min(i0 + r, N - 1)) * (size_t)D + 4 * kk;
+    const double* kp = kbar64 + (bh * N + min(j0 + r, N - 1)) * (size_t)D + 4 * kk;
+    f64x4 av[D / 16], bv[D / 16];
+#pragma unroll
+    for (int c = 0; c < D / 16; ++c) {
+      av[c] = *reinterpret_cast<const f64x4*>(qp + 16 * c);
+      bv[c] = *reinterpret_cast<const f64x4*>(kp + 16 * c);
+    }
+    f64x4 acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = acc0;
+#pragma unroll
+    for (int c = 0; c < D / 16; ++c)
+#pragma unroll
+      for (int u = 0; u < 4; u += 2) {
+        acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64(av[c][u], bv[c][u], acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64(av[c][u + 1], bv[c][u + 1], acc1, 0, 0, 0);
+      }
+    const int j = j0 + r;
+    if (j < N) {
+      const double bias = col_bias ? col_bias[bh * N + j] : 0.0;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) zs[4 * e + kk][j] = scale * (acc0[e] + acc1[e]) + bias;
+    }
+  }
+  __syncthreads();
+  const int i = i0 + wave;
+  if (i >= N) return;
+  const size_t row = bh * N + i;
+  topk_row<kFusedMaxN / 64>(zs[wave], N, k_top, hist_all[wave], idx + row * (size_t)k_top,
+                            kth_gap ? kth_gap + row : nullptr, lane);
 }
 
 }  // namespace
@@ -311,6 +367,16 @@ hipError_t launch_select(const Dims& dm, const double* qbar64, const double* kba
                          const double* col_bias, int k_top, int32_t* idx, float* kth_gap, double* zbuf,
                          hipStream_t stream) {
   const int nt = (dm.N + kZT - 1) / kZT;
+  if (dm.N <= kFusedMaxN) {                               // one launch for short sequences
+    const dim3 fgrid((dm.N + 15) / 16, dm.bh());
+    if (dm.d == 64)
+      hipLaunchKernelGGL(select_small_kernel<64>, fgrid, dim3(1024), 0, stream, qbar64, kbar64, col_bias, dm.N,
+                         (double)dm.scale, k_top, idx, kth_gap);
+    else
+      hipLaunchKernelGGL(select_small_kernel<128>, fgrid, dim3(1024), 0, stream, qbar64, kbar64, col_bias, dm.N,
+                         (double)dm.scale, k_top, idx, kth_gap);
+    return hipGetLastError();
+  }
   if ((size_t)nt * nt * dm.bh() < 1024) {                 // too few 64x64 tiles to fill the chip
     const int nt16 = (dm.N + 15) / 16;
     const dim3 sgrid((nt16 + 3) / 4, nt16, dm.bh());
