@@ -474,10 +474,11 @@ def test_out_of_range_index_entries_are_ignored(lib, dtype, d):
         assert rel <= TOL[q.dtype] and cos >= COS_MIN, (dtype, h, rel, cos)
 
 
-@pytest.mark.parametrize("N", [65, 512, 513, 1280, 1281, 2049, 4096])
+@pytest.mark.parametrize("N", [8, 17, 64, 100, 128, 129, 512, 513, 1280, 1281, 2049, 4096])
 def test_select_all_sizes_and_degenerate_rows(lib, N):
-    """pisa_select alone, at block counts on both sides of every keys-per-lane build of the
-    top-k kernel (up to the 4096-block maximum), on rows built to hit its special paths:
+    """pisa_select alone, at block counts on both sides of the one-launch limit (128) and of
+    every keys-per-lane build of the top-k kernel (up to the 4096-block maximum), on rows
+    built to hit its special paths:
     one sign only, a constant row, a row of two values, duplicates at the threshold, a huge
     dynamic range, and a column bias."""
     d, H = 64, 2
