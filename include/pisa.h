@@ -172,6 +172,17 @@ int32_t dense_attention(const pisa_shape* shape, const void* q, const void* k, c
  */
 int32_t pisa_probe_mfma_rate(int32_t iters, float* sink, size_t sink_floats, double* flop, void* stream);
 
+/*
+ * Measurement aid, not a step of the method: enqueues a one-wave kernel that reads the shader
+ * cycle counter and the device's constant-rate wall clock at the start and the end of a window
+ * of about window_ms milliseconds (in (0, 50]; the wave sleeps in between) and stores
+ * counts[0] = shader cycles, counts[1] = wall-clock ticks (device memory, 16-byte aligned,
+ * two entries).  *wall_clock_hz (host memory) receives the wall clock's rate, so that
+ * counts[0] / counts[1] * wall_clock_hz is the shader clock held during the window.  Launched
+ * on a second stream while an attention call runs, it reports the clock under that load.
+ */
+int32_t pisa_probe_shader_clock(double window_ms, uint64_t* counts, double* wall_clock_hz, void* stream);
+
 /* Message of the last failure on this thread ("" if none).  Never NULL. */
 const char* pisa_last_error(void);
 

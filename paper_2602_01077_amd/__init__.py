@@ -23,7 +23,7 @@ PISA_NORM_SPECTRAL, PISA_NORM_FROBENIUS = 0, 1
 
 EXPORTS = ("pisa_num_blocks", "pisa_topk_count", "pisa_workspace_bytes", "pisa_block_stats",
            "pisa_block_heterogeneity", "pisa_select", "pisa_attention", "dense_attention",
-           "pisa_probe_mfma_rate", "pisa_last_error")
+           "pisa_probe_mfma_rate", "pisa_probe_shader_clock", "pisa_last_error")
 
 
 class PisaShape(ctypes.Structure):
@@ -65,6 +65,8 @@ def _load() -> ctypes.CDLL:
     lib.dense_attention.restype = i32
     lib.pisa_probe_mfma_rate.argtypes = [i32, vp, sz, ctypes.POINTER(ctypes.c_double), vp]
     lib.pisa_probe_mfma_rate.restype = i32
+    lib.pisa_probe_shader_clock.argtypes = [ctypes.c_double, vp, ctypes.POINTER(ctypes.c_double), vp]
+    lib.pisa_probe_shader_clock.restype = i32
     lib.pisa_last_error.argtypes = []
     lib.pisa_last_error.restype = ctypes.c_char_p
     return lib
@@ -245,6 +247,16 @@ def probe_mfma_rate(iters: int, sink: torch.Tensor) -> float:
     _check(_lib.pisa_probe_mfma_rate(iters, _dev(sink, "sink", torch.float32), sink.numel(), ctypes.byref(flop),
                                      _stream()))
     return flop.value
+
+
+def probe_shader_clock(window_ms: float, counts: torch.Tensor) -> float:
+    """pisa_probe_shader_clock: enqueues the clock probe on the current stream; `counts` is an
+    int64 device tensor of two entries.  Returns the wall clock's rate in Hz; once the stream
+    has drained, counts[0] / counts[1] * rate is the shader clock held during the window."""
+    hz = ctypes.c_double(0.0)
+    _check(_lib.pisa_probe_shader_clock(float(window_ms), _dev(counts, "counts", torch.int64), ctypes.byref(hz),
+                                        _stream()))
+    return hz.value
 
 
 def pisa_forward(q, k, v, block: int = 64, sparsity: float = 0.85, first_order: bool = True,

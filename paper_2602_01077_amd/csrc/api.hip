@@ -239,6 +239,23 @@ int32_t pisa_probe_mfma_rate(int32_t iters, float* sink, size_t sink_floats, dou
   return PISA_OK;
 }
 
+int32_t pisa_probe_shader_clock(double window_ms, uint64_t* counts, double* wall_clock_hz, void* stream) {
+  if (!(window_ms > 0.0) || window_ms > 50.0)
+    return fail(PISA_INVALID_ARG, "window_ms = %g outside (0, 50]", window_ms);
+  if (!counts || !wall_clock_hz) return fail(PISA_INVALID_ARG, "counts and wall_clock_hz must not be NULL");
+  PISA_CHECK_ALIGN(counts);
+  int dev = 0, khz = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e == hipSuccess) e = hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev);
+  if (e != hipSuccess) return hip_fail("pisa_probe_shader_clock", e);
+  if (khz <= 0) return fail(PISA_UNSUPPORTED, "the device reports no wall-clock rate");
+  *wall_clock_hz = 1e3 * (double)khz;
+  const unsigned long long ticks = (unsigned long long)(window_ms * (double)khz);
+  e = launch_clock_probe(reinterpret_cast<unsigned long long*>(counts), ticks, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail("pisa_probe_shader_clock", e);
+  return PISA_OK;
+}
+
 const char* pisa_last_error(void) { return pisa::g_err; }
 
 }  // extern "C"

@@ -73,5 +73,7 @@ hipError_t launch_attention_bf16(const Dims& dm, const AttnArgs& a, hipStream_t 
 // Matrix-core rate probe: kProbeWorkgroups workgroups of 4 waves, 16 MFMAs per wave and iteration.
 constexpr int kProbeWorkgroups = 1024;
 hipError_t launch_mfma_probe(int iters, float* sink, hipStream_t stream);
+// Shader-clock probe: one wave, out = {shader cycles, wall-clock ticks} over `ticks` ticks.
+hipError_t launch_clock_probe(unsigned long long* out, unsigned long long ticks, hipStream_t stream);
 
 }  // namespace pisa

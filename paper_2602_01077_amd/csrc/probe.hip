@@ -1,6 +1,9 @@
-// Measurement aid: a register-only loop of v_mfma_f32_32x32x16_bf16, the instruction the
-// attention kernels are built on.  Timed by the caller, it gives the matrix-core rate this
-// chip sustains at its own clock, to set beside the published 2.5 PFLOP/s.
+// Measurement aids.  (1) A register-only loop of v_mfma_f32_32x32x16_bf16, the instruction
+// the attention kernels are built on: timed by the caller, it gives the matrix-core rate this
+// chip sustains at its own clock, to set beside the published 2.5 PFLOP/s.  (2) A one-wave
+// kernel that reads the shader-cycle counter and the constant-rate wall clock over a time
+// window: launched on a second stream while another kernel runs, it tells the shader clock
+// the chip holds under that kernel's load.
 #include "common.h"
 
 namespace pisa {
@@ -34,7 +37,30 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(int iters, float* __res
   sink[(size_t)blockIdx.x * 256 + tid] = s;
 }
 
+// out[0] = shader cycles, out[1] = wall-clock ticks over (about) `ticks` wall-clock ticks.
+// The wave sleeps between looks at the clock; `max_spins` bounds the loop whatever the clock does.
+__global__ __launch_bounds__(64) void clock_probe_kernel(unsigned long long* __restrict__ out,
+                                                         unsigned long long ticks, int max_spins) {
+  const unsigned long long c0 = __builtin_amdgcn_s_memtime();
+  const unsigned long long r0 = __builtin_amdgcn_s_memrealtime();
+  unsigned long long r1 = r0;
+  for (int spins = 0; spins < max_spins && r1 - r0 < ticks; ++spins) {
+    __builtin_amdgcn_s_sleep(127);
+    r1 = __builtin_amdgcn_s_memrealtime();
+  }
+  const unsigned long long c1 = __builtin_amdgcn_s_memtime();
+  if (threadIdx.x == 0) {
+    out[0] = c1 - c0;
+    out[1] = r1 - r0;
+  }
+}
+
 }  // namespace
+
+hipError_t launch_clock_probe(unsigned long long* out, unsigned long long ticks, hipStream_t stream) {
+  hipLaunchKernelGGL(clock_probe_kernel, dim3(1), dim3(64), 0, stream, out, ticks, 1 << 16);
+  return hipGetLastError();
+}
 
 hipError_t launch_mfma_probe(int iters, float* sink, hipStream_t stream) {
   hipLaunchKernelGGL(mfma_probe_kernel, dim3(kProbeWorkgroups), dim3(256), 0, stream, iters, sink);

@@ -129,6 +129,19 @@ def test_misaligned_pointers_are_rejected():
         == pisa.PISA_INVALID_ARG
 
 
+def test_probe_arguments_are_checked():
+    lib = pisa.raw()
+    hz = ctypes.c_double(0.0)
+    flop = ctypes.c_double(0.0)
+    assert lib.pisa_probe_shader_clock(0.0, FAKE, ctypes.byref(hz), None) == pisa.PISA_INVALID_ARG
+    assert lib.pisa_probe_shader_clock(51.0, FAKE, ctypes.byref(hz), None) == pisa.PISA_INVALID_ARG
+    assert lib.pisa_probe_shader_clock(float("nan"), FAKE, ctypes.byref(hz), None) == pisa.PISA_INVALID_ARG
+    assert lib.pisa_probe_shader_clock(1.0, None, ctypes.byref(hz), None) == pisa.PISA_INVALID_ARG
+    assert lib.pisa_probe_shader_clock(1.0, FAKE, None, None) == pisa.PISA_INVALID_ARG
+    assert lib.pisa_probe_mfma_rate(0, FAKE, 1 << 20, ctypes.byref(flop), None) == pisa.PISA_INVALID_ARG
+    assert lib.pisa_probe_mfma_rate(8, FAKE, 16, ctypes.byref(flop), None) == pisa.PISA_WORKSPACE_TOO_SMALL
+
+
 def test_binding_refuses_host_tensors():
     import torch
     q = torch.zeros(1, 2, 128, 64)

@@ -630,3 +630,15 @@ def test_wan_sweep_sampled(lib, block, r):
         assert rel <= TOL[q.dtype] and cos >= COS_MIN, (block, r, heads[slot], rel, cos)
         worst, cos_min = max(worst, rel), min(cos_min, cos)
     print(f"[parity] wan B={block} r={r} k={k_top}: pisa {worst:.2e} cos_min {cos_min:.6f}")
+
+
+def test_shader_clock_probe(lib):
+    """The clock probe (a measurement aid) returns a plausible shader clock and honours its window."""
+    counts = torch.zeros(2, dtype=torch.int64, device=DEV)
+    hz = lib.probe_shader_clock(2.0, counts)
+    torch.cuda.synchronize()
+    cyc, ticks = (int(x) for x in counts.cpu())
+    assert hz > 1e6
+    assert 0.9 * 2.0e-3 <= ticks / hz <= 5.0e-3, (ticks, hz)          # about the 2 ms asked for
+    ghz = cyc / ticks * hz / 1e9
+    assert 0.05 <= ghz <= 3.0, ghz
