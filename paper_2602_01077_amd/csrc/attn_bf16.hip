@@ -452,8 +452,9 @@ __device__ inline void absorb_tile(State<D>& st, const bf16x8 (&qreg)[D / 16], c
 
 // LDS map of the staging area (byte offsets): K stages | V stages; Phase 2 reuses it as
 // centroid keys (K stage 0) and centroid values (V stage 0).
+// Three workgroups per CU at head_dim 64 (168 VGPRs, 33 KB LDS each), two at 128.
 template <int D, bool DENSE>
-__global__ __launch_bounds__(256, 2) void attn_bf16_kernel(PB p) {
+__global__ __launch_bounds__(256, D == 64 ? 3 : 2) void attn_bf16_kernel(PB p) {
   constexpr int ROWB = Geo<D>::ROWB, TILEB = Geo<D>::TILEB, NKS = Geo<D>::NKS, NDT = Geo<D>::NDT;
   constexpr int CPR = Geo<D>::CPR, RPL = Geo<D>::RPL;
   constexpr int KST0 = 0, KST1 = TILEB, VST0 = 2 * TILEB, VST1 = 3 * TILEB;
