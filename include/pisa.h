@@ -165,7 +165,8 @@ int32_t dense_attention(const pisa_shape* shape, const void* q, const void* k, c
 /*
  * Measurement aid, not a step of the method: enqueues a register-only loop of the bf16
  * matrix instruction the attention kernels use (1024 workgroups x 4 waves x iters x 16
- * MFMAs of 32x32x16) and stores the floating-point operation count in *flop (host memory).
+ * MFMAs of 32x32x16, on pseudo-random operands in (-1, 1)) and stores the floating-point
+ * operation count in *flop (host memory).
  * The caller times the launch on `stream`; flop / time is the matrix-core rate the chip
  * sustains at its own clock, to quote beside the published peak.  `sink` is device memory of
  * at least 262144 floats (overwritten).  iters in [1, 2^24].

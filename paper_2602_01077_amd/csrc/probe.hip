@@ -12,14 +12,24 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
+__device__ inline unsigned mix32(unsigned x) {
+  x ^= x >> 16; x *= 0x7feb352dU; x ^= x >> 15; x *= 0x846ca68bU; x ^= x >> 16;
+  return x;
+}
+
+// Operands are pseudo-random bf16 values in (-1, 1), four A and four B fragments per lane used
+// in rotation, so that the switching activity in the operand paths resembles real data.
 __global__ __launch_bounds__(256) void mfma_probe_kernel(int iters, float* __restrict__ sink) {
-  const int tid = threadIdx.x;
-  bf16x8 a, b;
+  const unsigned tid = blockIdx.x * 256u + threadIdx.x;
+  bf16x8 a[4], b[4];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    a[e] = (__bf16)(0.001f * (float)((tid + e) & 7));
-    b[e] = (__bf16)(0.002f * (float)((tid + 3 * e) & 7));
-  }
+  for (int u = 0; u < 4; ++u)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const unsigned ha = mix32(tid * 64u + u * 8 + e), hb = mix32(0x9e3779b9u + tid * 64u + u * 8 + e);
+      a[u][e] = (__bf16)((float)((int)(ha & 0xffffu) - 32768) * (1.0f / 32768.f));
+      b[u][e] = (__bf16)((float)((int)(hb & 0xffffu) - 32768) * (1.0f / 32768.f));
+    }
   f32x16 acc[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) acc[i] = (f32x16){0};
@@ -27,14 +37,15 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(int iters, float* __res
 #pragma unroll
     for (int u = 0; u < 4; ++u)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+      for (int i = 0; i < 4; ++i)
+        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[(u + i) & 3], b[u], acc[i], 0, 0, 0);
   }
   float s = 0.f;
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int r = 0; r < 16; ++r) s += acc[i][r];
-  sink[(size_t)blockIdx.x * 256 + tid] = s;
+  sink[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
 }
 
 // out[0] = shader cycles, out[1] = wall-clock ticks over (about) `ticks` wall-clock ticks.
