@@ -50,7 +50,7 @@ def cpu_baseline(w, q, k, v, scale, k_top, budget_s=15.0):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = os.cpu_count() or 1
-    N = w.num_blocks
+    N = po.num_blocks(w.seq_len, w.block)
     rng = np.random.default_rng(0)
     t_start = time.perf_counter()
     t_stats = t_select = t_attn = 0.0
@@ -128,7 +128,8 @@ def main():
     q, k, v = make_qkv(w, device=dev)
     torch.cuda.synchronize()
     note(f"inputs ready: {w.name} {tuple(q.shape)} {w.dtype}")
-    N, k_top = w.num_blocks, w.topk
+    N = pisa.num_blocks(w.seq_len, w.block)
+    k_top = pisa.topk_count(N, w.sparsity)
     scale = pisa.resolved_scale(w.head_dim)
     shape = pisa.make_shape(q, w.block)
     ws = pisa.alloc_workspace(shape, dev)

@@ -47,7 +47,7 @@ def error_study(args):
         for name, kw in (("keep_or_drop", dict(approximate=False)),
                          ("zeroth_order", dict(first_order=False)),
                          ("hybrid", dict())):
-            if name == "keep_or_drop" and pisa.topk_count(w.num_blocks, r) == 0:
+            if name == "keep_or_drop" and pisa.topk_count(pisa.num_blocks(w.seq_len, w.block), r) == 0:
                 row[name] = None
                 continue
             out = pisa.pisa_forward(q, k, v, w.block, r, **kw)["out"]
@@ -68,8 +68,8 @@ def speed_study(args):
         dense_ms = _time_ms(lambda: pisa.dense_attention(q, k, v, w.block, out=out), args.iters)
         st = pisa.block_stats(q, k, v, w.block, ws)          # allocates the statistics tensors once
         for r in args.sparsity:
-            k_top = pisa.topk_count(w.num_blocks, r)
-            idx = torch.empty(q.shape[0], q.shape[1], w.num_blocks, k_top, dtype=torch.int32, device=dev)
+            k_top = pisa.topk_count(pisa.num_blocks(w.seq_len, w.block), r)
+            idx = torch.empty(q.shape[0], q.shape[1], pisa.num_blocks(w.seq_len, w.block), k_top, dtype=torch.int32, device=dev)
 
             def path():
                 pisa.block_stats_into(shape, q, k, v, st, ws)

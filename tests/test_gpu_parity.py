@@ -22,6 +22,16 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
+def wl_blocks(w):
+    """N of a workload, by the oracle's arithmetic."""
+    return po.num_blocks(w.seq_len, w.block)
+
+
+def wl_topk(w):
+    """k of a workload, by the oracle's arithmetic (the library's own count is checked against it)."""
+    return po.topk_count(wl_blocks(w), w.sparsity)
+
+
 def oracle_head(q, k, v, h, block, scale, k_top, per_block_H=False):
     Q, K, V = head_np(q, 0, h), head_np(k, 0, h), head_np(v, 0, h)
     st = po.block_stats(Q, K, V, block, per_block_H=per_block_H)
@@ -62,8 +72,8 @@ def run_full_case(pisa, w, blocks_per_head=None, heads=None, first_order=True, a
     dense, dense_lse = pisa.dense_attention(qd, kd, vd, w.block, want_lse=True)
     torch.cuda.synchronize()
     scale = pisa.resolved_scale(w.head_dim)
-    N, k_top = w.num_blocks, res["k_top"]
-    assert k_top == w.topk
+    N, k_top = wl_blocks(w), res["k_top"]
+    assert k_top == wl_topk(w)
     tol = TOL[q.dtype]
     mode = ("hybrid" if first_order else "pisa0") if approximate else "sparse"
     worst = dict(pisa=0.0, dense=0.0, cos=1.0)
@@ -171,7 +181,7 @@ def test_random_small_shapes(lib, i):
     dtype, d, B, L, r, mode, H = _random_case(i)
     w = WORKLOADS["flux"].with_(name=f"rand{i}-{dtype}-d{d}-{mode}", heads=H, seq_len=L, head_dim=d, dtype=dtype,
                                 block=B, sparsity=r, seed=500 + i, grid=None, block_offset_std=0.5)
-    if mode == "sparse" and w.topk == 0:
+    if mode == "sparse" and wl_topk(w) == 0:
         mode = "hybrid"                  # keep-or-drop needs at least one block
     run_full_case(lib, w, first_order=(mode == "hybrid"), approximate=(mode != "sparse"))
 
@@ -206,7 +216,7 @@ def test_batch_of_two(lib, dtype, d):
             st = po.block_stats(Q, K, V, w.block)
             idx_ref, gap_ref = po.select(st["qbar"], st["kbar"], scale, res["k_top"])
             idx_gpu = res["idx"][b, h].cpu().numpy()
-            check_select(idx_gpu, None, idx_ref, gap_ref, w.num_blocks, where=f" batch {b} head {h}")
+            check_select(idx_gpu, None, idx_ref, gap_ref, wl_blocks(w), where=f" batch {b} head {h}")
             ref, _ = po.attention_head(Q, K, V, w.block, idx_gpu, scale, "hybrid", stats=st)
             rel, cos = row_errors(res["out"][b, h].float().cpu().numpy(), ref)
             assert rel <= TOL[q.dtype] and cos >= COS_MIN, (b, h, rel, cos)
@@ -221,7 +231,7 @@ def test_all_blocks_selected_is_bitwise_dense(lib, dtype, d, B):
     res = lib.pisa_forward(q, k, v, B, 0.0, want_lse=True)
     dense, lse = lib.dense_attention(q, k, v, B, want_lse=True)
     torch.cuda.synchronize()
-    assert res["k_top"] == w.num_blocks
+    assert res["k_top"] == wl_blocks(w)
     assert torch.equal(res["out"], dense)
     assert torch.equal(res["lse"], lse)
 
@@ -238,7 +248,7 @@ def test_covariance_aware_selection(lib, dtype, d, B, L):
     scale = lib.resolved_scale(d)
     shape = lib.make_shape(qd, B)
     st_gpu = lib.block_stats(qd, kd, vd, B)
-    N, k_top = w.num_blocks, w.topk
+    N, k_top = wl_blocks(w), wl_topk(w)
     # Frobenius is exact (fp64); the spectral norm comes from 48 power-iteration steps, which
     # approach the largest singular value from below and, for these nearly-flat spectra
     # (rank <= block size, closely spaced singular values), stop a few percent short.
@@ -281,7 +291,7 @@ def test_three_calls_replay_from_a_hip_graph(lib):
     w = WORKLOADS["flux"].with_(heads=4, seq_len=3000, grid=None)
     q, k, v = (x.to(DEV) for x in make_qkv(w))
     shape = lib.make_shape(q, w.block)
-    N, k_top = w.num_blocks, w.topk
+    N, k_top = wl_blocks(w), wl_topk(w)
     ws = lib.alloc_workspace(shape, DEV)
     st = lib.block_stats(q, k, v, w.block, ws)          # also allocates the output tensors
     idx = torch.empty(1, w.heads, N, k_top, dtype=torch.int32, device=DEV)
@@ -330,7 +340,7 @@ def test_custom_softmax_scale(lib, dtype, d, scale):
     res = lib.pisa_forward(qd, kd, vd, w.block, w.sparsity, want_lse=True, scale=scale)
     dense, _ = lib.dense_attention(qd, kd, vd, w.block, scale=scale)
     torch.cuda.synchronize()
-    N, k_top = w.num_blocks, w.topk
+    N, k_top = wl_blocks(w), wl_topk(w)
     for h in range(w.heads):
         Q, K, V, st, idx_ref, gap_ref = oracle_head(q, k, v, h, w.block, s32, k_top)
         idx_gpu = res["idx"][0, h].cpu().numpy()
@@ -457,7 +467,7 @@ def test_out_of_range_index_entries_are_ignored(lib, dtype, d):
     scale = lib.resolved_scale(d)
     ws = lib.alloc_workspace(shape, DEV)
     st = lib.block_stats(qd, kd, vd, w.block, ws)
-    N, k_top = w.num_blocks, w.topk
+    N, k_top = wl_blocks(w), wl_topk(w)
     idx, _ = lib.select(shape, st["qbar64"], st["kbar64"], k_top, ws)
     bad = idx.clone()
     bad[..., -1] = N + 7                 # past the end
@@ -521,7 +531,7 @@ def test_select_all_sizes_and_degenerate_rows(lib, N):
 
 
 def _sampled_blocks(w, rng, extra=()):
-    N = w.num_blocks
+    N = wl_blocks(w)
     fixed = {0, N - 1, *extra}
     rand = set(rng.choice(N, size=14, replace=False).tolist())
     return sorted(fixed | rand)
@@ -539,7 +549,7 @@ def test_video_configs_sampled(lib, name):
     res = lib.pisa_forward(q, k, v, w.block, w.sparsity, want_lse=True)
     dense, _ = lib.dense_attention(q, k, v, w.block)
     torch.cuda.synchronize()
-    N, k_top = w.num_blocks, w.topk
+    N, k_top = wl_blocks(w), wl_topk(w)
     rng = np.random.default_rng(99)
     out_heads = set(rng.choice(w.heads, size=8, replace=False).tolist())
     n_grid = int(np.prod(w.grid))
@@ -573,13 +583,13 @@ def test_maximum_block_count(lib, block, L):
     outputs on sampled query blocks including the first and the last."""
     w = WORKLOADS["wan"].with_(name=f"max-blocks-{block}", heads=1, seq_len=L, block=block, grid=None,
                                sparsity=0.98)
-    assert w.num_blocks == 4096
+    assert wl_blocks(w) == 4096
     scale = lib.resolved_scale(w.head_dim)
     q, k, v = make_qkv(w, device=DEV)
     res = lib.pisa_forward(q, k, v, block, w.sparsity, want_lse=True)
     dense, _ = lib.dense_attention(q, k, v, block)
     torch.cuda.synchronize()
-    N, k_top = w.num_blocks, w.topk
+    N, k_top = wl_blocks(w), wl_topk(w)
     Q, K, V, st, idx_ref, gap_ref = oracle_head(q, k, v, 0, block, scale, k_top)
     check_stats(res["stats"], st, 0, q.dtype)
     idx_gpu = res["idx"][0, 0].cpu().numpy()
@@ -607,7 +617,7 @@ def test_wan_sweep_sampled(lib, block, r):
     q, k, v = make_qkv(w, device=DEV, heads=heads)
     res = lib.pisa_forward(q, k, v, block, r)
     torch.cuda.synchronize()
-    N, k_top = w.num_blocks, w.topk
+    N, k_top = wl_blocks(w), wl_topk(w)
     assert res["k_top"] == k_top
     if r == 0.0:
         dense, _ = lib.dense_attention(q, k, v, block)

@@ -438,3 +438,64 @@ def test_covariance_bias_is_neutral_when_blocks_are_alike():
     assert np.all((biased == 5).any(axis=1))     # every query block now keeps block 5 exact
     flat, _ = po.select(st["qbar"], st["kbar"], 0.5, 2, col_bias=np.full(N, math.log(others[0])))
     assert np.array_equal(flat, plain)
+
+
+# --- keep-or-drop at k < N is the masked softmax of the Preliminaries ----------------
+@pytest.mark.parametrize("L,B,k", [(96, 16, 2), (90, 16, 3), (90, 16, 1)])
+def test_sparse_mode_is_block_masked_library_attention(L, B, k):
+    """Preliminaries, second equation: keep-or-drop attention is dense attention with a
+    mask of 0 on the selected blocks' tokens and -inf elsewhere.  Checked against torch's
+    fp64 CPU attention routine fed that additive mask (ragged last block included)."""
+    d = 8
+    Q, K, V = rand_qkv(L, d)
+    s = 1 / math.sqrt(d)
+    N = po.num_blocks(L, B)
+    idx = random_idx(N, k)
+    blk_q = np.arange(L) // B
+    blk_k = np.arange(L) // B
+    keep = np.zeros((L, L), dtype=bool)
+    for i in range(N):
+        keep[np.ix_(blk_q == i, np.isin(blk_k, idx[i]))] = True
+    mask = np.where(keep, 0.0, -np.inf)
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(Q)[None], torch.from_numpy(K)[None], torch.from_numpy(V)[None],
+        attn_mask=torch.from_numpy(mask)[None], scale=s)[0].numpy()
+    O, lse = po.attention_head(Q, K, V, B, idx, s, "sparse")
+    assert np.abs(O - ref).max() < 1e-12
+    ref_lse = torch.logsumexp(torch.from_numpy(s * (Q @ K.T) + mask), dim=1).numpy()
+    assert np.abs(lse - ref_lse).max() < 1e-12
+    # and it is NOT the dense result (the mask matters at k < N)
+    Od, _ = po.attention_head(Q, K, V, B, None, s, "dense")
+    assert np.abs(O - Od).max() > 1e-3
+
+
+# --- rank-one blocks give the heterogeneity in closed form ----------------------------
+@pytest.mark.parametrize("L,B", [(96, 16), (90, 16)])
+def test_heterogeneity_closed_form_rank_one(L, B):
+    """Covariance-Aware Block Selection: M_j = ||H_j - Hbar||.  Keys k_{j,n} = c_j + u_n a and
+    values v_{j,n} = g_j u_n b / sum_n u_n^2 + w (sum_n u_n = 0 inside every block) give
+    H_j = g_j a^T b exactly, so Hbar = mean(g) a^T b and
+    M_j = |g_j - mean(g)| ||a|| ||b|| in the spectral and in the Frobenius norm alike."""
+    d = 5
+    rng = np.random.default_rng(31)
+    N = po.num_blocks(L, B)
+    sizes = po.block_sizes(L, B)
+    a, b, w = rng.standard_normal(d), rng.standard_normal(d), rng.standard_normal(d)
+    g = rng.standard_normal(N) * 3.0
+    cent = rng.standard_normal((N, d))
+    K = np.empty((L, d))
+    V = np.empty((L, d))
+    for j in range(N):
+        u = rng.standard_normal(sizes[j])
+        u -= u.mean()
+        lo = j * B
+        K[lo:lo + sizes[j]] = cent[j] + np.outer(u, a)
+        V[lo:lo + sizes[j]] = g[j] * np.outer(u, b) / (u @ u) + w
+    Q = rng.standard_normal((L, d))
+    st = po.block_stats(Q, K, V, B, per_block_H=True)
+    for j in range(N):
+        assert np.abs(st["Hj"][j] - g[j] * np.outer(a, b)).max() < 1e-12
+    want = np.abs(g - g.mean()) * np.linalg.norm(a) * np.linalg.norm(b)
+    for kind in ("spectral", "frobenius"):
+        M = po.block_heterogeneity(st["Hj"], st["hsum"], kind)
+        assert np.abs(M - want).max() < 1e-11 * max(1.0, want.max())

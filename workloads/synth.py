@@ -101,15 +101,6 @@ class Workload:
     field_terms: int = 4
     field_fmax: float = 0.2
 
-    @property
-    def num_blocks(self) -> int:
-        return -(-self.seq_len // self.block)
-
-    @property
-    def topk(self) -> int:
-        n = self.num_blocks
-        return n - int(math.floor(self.sparsity * n + 1e-9))
-
     def with_(self, **kw) -> "Workload":
         d = dict(self.__dict__)
         d.update(kw)
@@ -173,7 +164,7 @@ def _field(w: Workload, head: int, device) -> Optional[torch.Tensor]:
 def _block_offsets(w: Workload, head: int, device) -> Optional[torch.Tensor]:
     if w.block_offset_std <= 0.0:
         return None
-    n, d = w.num_blocks, w.head_dim
+    n, d = -(-w.seq_len // w.block), w.head_dim      # one offset vector per run of `block` tokens
     key = _stream_key(w.seed, _TID_OFFSET, head)
     off = _normal(key, n * d, device).reshape(n, d) * w.block_offset_std
     return off.repeat_interleave(w.block, dim=0)[: w.seq_len]
