@@ -190,6 +190,9 @@ struct LaneCtx {
 // (wave-uniform).  The LDS-DMA instruction goes through inline asm on purpose: the compiler
 // then does not track it and puts no vmcnt wait in front of LDS reads of the other stage;
 // completion is enforced by wait_async_loads() + barrier before a stage is read.
+// The instruction takes its LDS base from M0; a scalar write of M0 needs one wait state before
+// an LDS-DMA instruction reads it, and the compiler cannot see inside the asm string, so the
+// s_nop is written out.
 // rows_avail < 64: rows past the end are replaced by the last valid row (finite data; such
 // keys are masked by the caller).
 template <int D, bool KFMT>
@@ -201,7 +204,7 @@ __device__ inline void load_tile_async(const LaneCtx& lc, const unsigned char* t
   if (rows_avail >= kTile) {
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
-      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                    :
                    : "s"(m0_0 + i * 4096), "v"(voff), "s"(tile_base + i * 4096)
                    : "memory", "m0");
@@ -212,7 +215,7 @@ __device__ inline void load_tile_async(const LaneCtx& lc, const unsigned char* t
       const int r = lc.dma_r0 + 4 * RPL * i;
       const int back = max(r - (rows_avail - 1), 0);                    // rows to step back
       const unsigned char* src = tile_base + i * 4096 + (long long)voff - (long long)back * ROWB;
-      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
                    :
                    : "s"(m0_0 + i * 4096), "v"(src)
                    : "memory", "m0");
@@ -226,7 +229,7 @@ template <bool KFMT>
 __device__ inline void load_tile_part(const LaneCtx& lc, const unsigned char* tile_base, unsigned lds_stage, int i) {
   const unsigned voff = KFMT ? lc.dma_k : lc.dma_v;
   const unsigned m0_0 = __builtin_amdgcn_readfirstlane(lds_stage + lc.wave * 1024);
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                :
                : "s"(m0_0 + i * 4096), "v"(voff), "s"(tile_base + i * 4096)
                : "memory", "m0");
@@ -471,7 +474,10 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void attn_bf16_kernel(PB p) {
   const int wg = blockIdx.x;
   int item = ((wg >> 6) << 6) + ((wg & 7) << 3) + ((wg >> 3) & 7);   // 8 neighbours per XCD
   if (DENSE) {
+    // The grid is rounded up, so ids with wg / 8 >= per_xcd would spill into the next XCD's
+    // range and redo its first items: they leave.
     const int per_xcd = (p.total + 7) / 8;
+    if (wg / 8 >= per_xcd) return;
     item = (wg % 8) * per_xcd + wg / 8;
   }
   if (item >= p.total) return;
