@@ -57,7 +57,9 @@ typedef struct pisa_shape {
   float   scale;      /* softmax scale s; <= 0 selects 1/sqrt(head_dim) */
 } pisa_shape;
 
-/* N = ceil(seq_len / block); returns -1 on non-positive arguments. */
+/* Alg. 1 (the loop over query blocks i = 1 .. ceil(L / B)): the number of blocks
+ * N = ceil(seq_len / block) on the query and on the key/value side alike.
+ * Returns -1 on non-positive arguments. */
 int32_t pisa_num_blocks(int32_t seq_len, int32_t block);
 
 /* Number k of exactly-attended blocks at sparsity r (Experiments, "Implementation
