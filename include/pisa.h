@@ -159,6 +159,28 @@ int32_t pisa_attention(const pisa_shape* shape, const void* q, const void* k, co
                        void* out, float* lse,
                        void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * pisa_attention for callers that cannot allocate or carry a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * kernels and the same result bit for bit; the scratch (bf16 centroid tiles, packed hsum,
+ * column bias) lives in a device array inside the library of PISA_STATIC_SCRATCH_BYTES, which
+ * every GPU the library runs on holds until the process ends.  The call allocates and frees
+ * nothing and does not synchronise.
+ *   - Shapes whose scratch need (batch * heads * (4 * ceil(N / 64) * 64 * d + 4 * d * d) bytes
+ *     + 4 * ceil(N / 64) * 64, bf16 path) exceeds the array return PISA_WORKSPACE_TOO_SMALL before
+ *     any device work; the three bf16 shapes of the paper's models fit.
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU
+ *     (different streams, or threads) race on it.  Calls on one stream are ordered and safe.
+ *     Nothing in the array has to be cleared between calls: each call rewrites all it reads.
+ *   - The array's address is looked up on the first call on each device; make that call
+ *     outside a stream capture.
+ */
+#define PISA_STATIC_SCRATCH_BYTES (32u << 20)
+int32_t pisa_attention_static(const pisa_shape* shape, const void* q, const void* k, const void* v,
+                              const float* kbar, const float* vsum, const float* hsum,
+                              const int32_t* idx, int32_t k_top,
+                              void* out, float* lse, void* stream);
+
 /* Preliminaries, first equation: out = softmax(s Q K^T) V with an online softmax over
  * 64-key tiles; lse as above (may be NULL).  shape->block only sets the tile walk. */
 int32_t dense_attention(const pisa_shape* shape, const void* q, const void* k, const void* v,

@@ -22,7 +22,8 @@ PISA_FP32, PISA_BF16 = 0, 1
 PISA_NORM_SPECTRAL, PISA_NORM_FROBENIUS = 0, 1
 
 EXPORTS = ("pisa_num_blocks", "pisa_topk_count", "pisa_workspace_bytes", "pisa_block_stats",
-           "pisa_block_heterogeneity", "pisa_select", "pisa_attention", "dense_attention",
+           "pisa_block_heterogeneity", "pisa_select", "pisa_attention", "pisa_attention_static",
+           "dense_attention",
            "pisa_probe_mfma_rate", "pisa_probe_shader_clock", "pisa_last_error")
 
 
@@ -61,6 +62,8 @@ def _load() -> ctypes.CDLL:
     lib.pisa_select.restype = i32
     lib.pisa_attention.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
     lib.pisa_attention.restype = i32
+    lib.pisa_attention_static.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp]
+    lib.pisa_attention_static.restype = i32
     lib.dense_attention.argtypes = [shp, vp, vp, vp, vp, vp, vp]
     lib.dense_attention.restype = i32
     lib.pisa_probe_mfma_rate.argtypes = [i32, vp, sz, ctypes.POINTER(ctypes.c_double), vp]
@@ -222,6 +225,22 @@ def attention(shape: PisaShape, q, k, v, kbar, vsum, hsum, idx, k_top: int,
         _dev(idx, "idx", torch.int32) if k_top > 0 else None, k_top,
         _dev(out, "out", like=q), _dev(lse, "lse", torch.float32),
         _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream()))
+    return out, lse
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def attention_static(shape: PisaShape, q, k, v, kbar, vsum, hsum, idx, k_top: int,
+                     out: torch.Tensor, lse: Optional[torch.Tensor] = None):
+    """pisa_attention_static: pisa_attention on the library's built-in scratch array; the
+    caller passes every buffer (nothing is allocated here either).  Returns (out, lse)."""
+    _check(_lib.pisa_attention_static(
+        ctypes.byref(shape), _dev(q, "q"), _dev(k, "k", like=q), _dev(v, "v", like=q),
+        _dev(kbar, "kbar", torch.float32), _dev(vsum, "vsum", torch.float32),
+        _dev(hsum, "hsum", torch.float32),
+        _dev(idx, "idx", torch.int32) if k_top > 0 else None, k_top,
+        _dev(out, "out", like=q), _dev(lse, "lse", torch.float32), _stream()))
     return out, lse
 
 

@@ -216,6 +216,39 @@ int32_t pisa_attention(const pisa_shape* shape, const void* q, const void* k, co
   return run_attention(dm, a, stream, "pisa_attention");
 }
 
+int32_t pisa_attention_static(const pisa_shape* shape, const void* q, const void* k, const void* v,
+                              const float* kbar, const float* vsum, const float* hsum,
+                              const int32_t* idx, int32_t k_top, void* out, float* lse, void* stream) {
+  Dims dm;
+  int32_t rc = resolve(shape, &dm);
+  if (rc != PISA_OK) return rc;
+  if (!q || !k || !v || !out) return fail(PISA_INVALID_ARG, "q, k, v, out must not be NULL");
+  if (k_top < 0 || k_top > dm.N)
+    return fail(PISA_INVALID_ARG, "k_top = %d outside [0, N = %d]", k_top, dm.N);
+  if (k_top > 0 && !idx) return fail(PISA_INVALID_ARG, "idx is NULL but k_top > 0");
+  if ((kbar == nullptr) != (vsum == nullptr))
+    return fail(PISA_INVALID_ARG, "kbar and vsum must both be given or both be NULL");
+  if (!kbar && k_top == 0)
+    return fail(PISA_INVALID_ARG, "keep-or-drop mode (kbar == vsum == NULL) needs k_top >= 1");
+  PISA_CHECK_ALIGN(q, k, v, kbar, vsum, hsum, idx, out, lse);
+  if (dm.N > kMaxBlocks)
+    return fail(PISA_UNSUPPORTED, "at most %d blocks are supported (N = %d)", kMaxBlocks, dm.N);
+  void* ws = nullptr;
+  if (k_top < dm.N && kbar) {
+    const size_t need = attention_workspace_bytes(dm);
+    if (need > kStaticScratchBytes)
+      return fail(PISA_WORKSPACE_TOO_SMALL,
+                  "this shape needs %zu bytes of scratch, the built-in array holds %zu: use pisa_attention "
+                  "with a caller-owned workspace", need, (size_t)kStaticScratchBytes);
+    if (need > 0) {
+      hipError_t e = static_scratch_ptr(&ws);
+      if (e != hipSuccess) return hip_fail("pisa_attention_static (address of the scratch array)", e);
+    }
+  }
+  AttnArgs a{q, k, v, kbar, vsum, hsum, idx, k_top, out, lse, false, ws};
+  return run_attention(dm, a, stream, "pisa_attention_static");
+}
+
 int32_t dense_attention(const pisa_shape* shape, const void* q, const void* k, const void* v,
                         void* out, float* lse, void* stream) {
   Dims dm;

@@ -34,6 +34,7 @@
 // traffic per flop.  Phase 2 streams bf16 centroid tiles prepared by a small pre-pass
 // (kbar_j rounded to bf16, the precision the keys themselves arrive in; vsum_j / B_j;
 // log2 B_j), Phase 3 multiplies by the pre-packed hi/lo split of hsum.
+#include <mutex>
 #include <type_traits>
 
 #include "common.h"
@@ -803,6 +804,33 @@ static hipError_t launch_attention_bf16_d(const Dims& dm, const AttnArgs& a, hip
   }
   hipLaunchKernelGGL((attn_bf16_kernel<D, false>), dim3(grid), dim3(256), 0, stream, p);
   return hipGetLastError();
+}
+
+// Device scratch for callers that cannot hand over a workspace (pisa_attention_static): the
+// centroid tiles, the packed hsum and the bias vector of one call.  Every device the library
+// runs on holds its own copy of the array until the process ends.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// In host code `scratch` is only a handle: the array's device address is looked up once per
+// device (with that device current) and kept; kernels and copies get that pointer.
+hipError_t static_scratch_ptr(void** out) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* ptr[kMaxDevices] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    ptr[dev] = p;
+  }
+  *out = ptr[dev];
+  return hipSuccess;
 }
 
 hipError_t launch_attention_bf16(const Dims& dm, const AttnArgs& a, hipStream_t stream) {

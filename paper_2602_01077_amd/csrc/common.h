@@ -67,6 +67,10 @@ struct AttnArgs {
   void* workspace;       // scratch for the bf16 PISA pre-pass (null for dense / fp32)
 };
 size_t attention_workspace_bytes(const Dims& dm);
+// Size of the file-scope device array behind pisa_attention_static, and its address on the
+// current device (resolved on first use, once per device).
+constexpr size_t kStaticScratchBytes = PISA_STATIC_SCRATCH_BYTES;
+hipError_t static_scratch_ptr(void** out);
 hipError_t launch_attention_fp32(const Dims& dm, const AttnArgs& a, hipStream_t stream);
 hipError_t launch_attention_bf16(const Dims& dm, const AttnArgs& a, hipStream_t stream);
 
