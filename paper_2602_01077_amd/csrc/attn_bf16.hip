@@ -224,16 +224,33 @@ __device__ inline void load_tile_async(const LaneCtx& lc, const unsigned char* t
   }
 }
 
-// Load i of this wave's share of a FULL tile: the same instruction as in load_tile_async,
-// one at a time.
-template <bool KFMT>
-__device__ inline void load_tile_part(const LaneCtx& lc, const unsigned char* tile_base, unsigned lds_stage, int i) {
+// One trip of the Phase-1 walk fills a 64-row stage in two halves of 32 rows: `lo` and `hi`
+// are the byte offsets (from the head's K or V base) of the sources of stage rows 0..31 and
+// 32..63.  Both halves of one tile (hi = lo + half a tile) make an ordinary full-tile trip;
+// in a split trip the two halves come from different tiles (see the trip list in the kernel).
+struct Trip {
+  int lo, hi;
+};
+
+// Load i of this wave's share of a stage: the LDS-DMA instruction of load_tile_async, one at a
+// time; the first half of a wave's loads falls into stage rows 0..31 and reads `lo`, the rest `hi`.
+template <int D, bool KFMT>
+__device__ inline void load_stage_part(const LaneCtx& lc, const unsigned char* g, const Trip t,
+                                       unsigned lds_stage, int i) {
+  constexpr int HALF = Geo<D>::NLD / 2;
   const unsigned voff = KFMT ? lc.dma_k : lc.dma_v;
   const unsigned m0_0 = __builtin_amdgcn_readfirstlane(lds_stage + lc.wave * 1024);
+  const int off = __builtin_amdgcn_readfirstlane(i < HALF ? t.lo + i * 4096 : t.hi + (i - HALF) * 4096);
+  const unsigned char* src = g + off;
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                :
-               : "s"(m0_0 + i * 4096), "v"(voff), "s"(tile_base + i * 4096)
+               : "s"(m0_0 + i * 4096), "v"(voff), "s"(src)
                : "memory", "m0");
+}
+template <int D, bool KFMT>
+__device__ inline void load_stage(const LaneCtx& lc, const unsigned char* g, const Trip t, unsigned lds_stage) {
+#pragma unroll
+  for (int i = 0; i < Geo<D>::NLD; ++i) load_stage_part<D, KFMT>(lc, g, t, lds_stage, i);
 }
 
 // V-format swizzle: the 32-byte chunk index of row r is XORed with this 3-bit value.  The
@@ -258,6 +275,12 @@ __device__ inline LDS_PTR(const unsigned char) xor_ptr(LDS_PTR(const unsigned ch
 
 // s_waitcnt vmcnt(0) with the other counters left alone (gfx9 encoding).
 __device__ inline void wait_async_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+// s_waitcnt vmcnt(N): returns once at most the N youngest of this wave's loads are still in
+// flight (they complete in the order issued).  gfx9 encoding: vmcnt in bits 3..0 and 15..14.
+template <int N> __device__ inline void wait_older_loads() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
 
 // ---- the three stages of one 64-key tile ------------------------------------------------
 // LDS offsets (KOFF, VOFF) are compile-time and relative to the staging origin the
@@ -279,33 +302,16 @@ __device__ inline void qk_tile(f32x16& s0, f32x16& s1, const bf16x8 (&qreg)[D / 
   }
 }
 
-// qk_tile with the LDS-DMA loads of the next K / V tiles issued between its MFMAs, so
-// that the issue cost of a load hides under a running MFMA.  K operands are read one step
-// ahead of their use (the loads order LDS reads around them).
-template <int D, int KOFF>
-__device__ inline void qk_tile_dma(f32x16& s0, f32x16& s1, const bf16x8 (&qreg)[D / 16], const LaneCtx& lc,
-                                   const unsigned char* kt, unsigned k_stage, const unsigned char* vt,
-                                   unsigned v_stage) {
-  constexpr int ROWB = Geo<D>::ROWB, NKS = Geo<D>::NKS, NLD = Geo<D>::NLD;
-  static_assert(2 * NLD <= NKS, "the loads of both tiles must fit between the contraction steps");
-  s0 = (f32x16){0};
-  s1 = (f32x16){0};
-  bf16x8 a0 = *reinterpret_cast<LDS_PTR(const bf16x8)>(lc.kbase + KOFF);
-  bf16x8 a1 = *reinterpret_cast<LDS_PTR(const bf16x8)>(lc.kbase + KOFF + 32 * ROWB);
+// One half of it: the 32 keys of stage rows ROW0 .. ROW0 + 31 (ROW0 = 0 or 32).
+template <int D, int KOFF, int ROW0>
+__device__ inline void qk_rows(f32x16& s, const bf16x8 (&qreg)[D / 16], const LaneCtx& lc) {
+  constexpr int ROWB = Geo<D>::ROWB;
+  s = (f32x16){0};
 #pragma unroll
-  for (int ks = 0; ks < NKS; ++ks) {
-    bf16x8 n0 = a0, n1 = a1;
-    if (ks < NKS - 1) {
-      LDS_PTR(const unsigned char) kp = xor_ptr(lc.kbase, (ks + 1) << 5);
-      n0 = *reinterpret_cast<LDS_PTR(const bf16x8)>(kp + KOFF);
-      n1 = *reinterpret_cast<LDS_PTR(const bf16x8)>(kp + KOFF + 32 * ROWB);
-    }
-    s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qreg[ks], s0, 0, 0, 0);
-    s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qreg[ks], s1, 0, 0, 0);
-    if (ks < NLD) load_tile_part<true>(lc, kt, k_stage, ks);
-    else if (ks < 2 * NLD) load_tile_part<false>(lc, vt, v_stage, ks - NLD);
-    a0 = n0;
-    a1 = n1;
+  for (int ks = 0; ks < D / 16; ++ks) {
+    LDS_PTR(const unsigned char) kp = xor_ptr(lc.kbase, ks << 5);
+    const bf16x8 a = *reinterpret_cast<LDS_PTR(const bf16x8)>(kp + KOFF + ROW0 * ROWB);
+    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], s, 0, 0, 0);
   }
 }
 
@@ -389,35 +395,57 @@ __device__ inline void softmax_exp(State<D>& st, const f32x16& s0, const f32x16&
   }
 }
 
-// Fast step for a full exact tile: probabilities against the running max AS IT STANDS (no
+// Fast step for full exact keys: probabilities against the running max AS IT STANDS (no
 // new maximum is taken, so no cross-lane exchange and no rescale), packed to bf16, with
 // their row-sum.  fp32 and bf16 share their exponent range, so a stale maximum costs no
 // accuracy until 2^(logit - max) nears overflow: the caller falls back to the exact step
-// (softmax_max, then this again) when some lane's sum is not below kStaleLimit.  Sums stay
+// (the true maximum, then this again) when some lane's sum is not below kStaleLimit.  Sums stay
 // below 2^60 between refreshes, so l and O (at most a few 10^5 keys of bounded values) stay
 // far from the fp32 limit.  A wave that has absorbed nothing yet (max = -inf) gets +inf
 // everywhere and therefore always falls back on its first tile; NaN falls back as well.
+// The work comes in halves of 32 keys (one S^T accumulator -> two B operands of 16 keys), so
+// that a wave can take either half of a stage or both; pa / pc carry the two partial sums
+// through the halves in a fixed order.
 constexpr float kStaleLimit = 0x1p60f;
-template <int D>
-__device__ inline float softmax_exp_stale(const State<D>& st, const f32x16& s0, const f32x16& s1,
-                                         bf16x8 (&pb)[4], float c) {
-  const float nm = -st.m;
-  float pa = 0.f, pc = 0.f;
+__device__ inline void exp_rows(const f32x16& s, float c, float nm, bf16x8& p0, bf16x8& p1, float& pa, float& pc) {
 #pragma unroll
-  for (int step = 0; step < 4; ++step) {            // keys 16 step .. 16 step + 15
+  for (int step = 0; step < 2; ++step) {            // keys 16 step .. 16 step + 15 of the half
     u32x4 pw;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int r = (8 * step + 2 * i) & 15;        // registers r, r + 1 of s0 (steps 0, 1) or s1
-      const float x0 = __builtin_amdgcn_exp2f(fmaf(step < 2 ? s0[r] : s1[r], c, nm));
-      const float x1 = __builtin_amdgcn_exp2f(fmaf(step < 2 ? s0[r + 1] : s1[r + 1], c, nm));
+      const int r = 8 * step + 2 * i;
+      const float x0 = __builtin_amdgcn_exp2f(fmaf(s[r], c, nm));
+      const float x1 = __builtin_amdgcn_exp2f(fmaf(s[r + 1], c, nm));
       pw[i] = pack_bf16(x0, x1);
       if (i & 1) pc += x0 + x1;
       else pa += x0 + x1;
     }
-    pb[step] = __builtin_bit_cast(bf16x8, pw);
+    if (step == 0) p0 = __builtin_bit_cast(bf16x8, pw);
+    else p1 = __builtin_bit_cast(bf16x8, pw);
   }
-  return pa + pc;
+}
+// Largest raw accumulator of one half.
+__device__ inline float max_rows(const f32x16& s) {
+  float t = s[0];
+#pragma unroll
+  for (int r = 1; r < 16; ++r) t = fmaxf(t, s[r]);
+  return t;
+}
+// Exact step: the running max takes in `tmax` (this lane's largest new logit, log2 domain);
+// l, l_tail and O are rescaled if some lane's max moved.
+template <int D>
+__device__ inline void raise_max(State<D>& st, float tmax) {
+  tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+  const float m_new = fmaxf(st.m, tmax);
+  const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+  if (__any(m_new != st.m)) {
+    const float corr = __builtin_amdgcn_exp2f(st.m - m_safe);
+    st.l *= corr;
+    st.l_tail *= corr;
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt) st.ot[dt] *= corr;
+    st.m = m_new;
+  }
 }
 
 // O^T += V^T P^T: four contraction steps of 16 keys.  Transposed LDS read: lane j of a
@@ -442,6 +470,26 @@ __device__ inline void pv_tile(State<D>& st, const bf16x8 (&pb)[4], const LaneCt
   }
 }
 
+// Two of those contraction steps: the 32 keys of stage rows ROW0 .. ROW0 + 31.
+template <int D, int VOFF, int ROW0>
+__device__ inline void pv_rows(State<D>& st, const bf16x8& p0, const bf16x8& p1, const LaneCtx& lc) {
+  constexpr int ROWB = Geo<D>::ROWB;
+#pragma unroll
+  for (int step = 0; step < 2; ++step) {
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt) {
+      LDS_PTR(unsigned char) vp =
+          const_cast<LDS_PTR(unsigned char)>(xor_ptr(lc.vbase, dt << 6)) + VOFF + (ROW0 + 16 * step) * ROWB;
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<LDS_PTR(s16x4)>(vp));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<LDS_PTR(s16x4)>(vp + 8 * ROWB));
+      const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
+      const u32x4 aw = {l2.x, l2.y, h2.x, h2.y};
+      st.ot[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, aw), step == 0 ? p0 : p1,
+                                                          st.ot[dt], 0, 0, 0);
+    }
+  }
+}
+
 // One staged tile, start to finish (ragged tile, centroid tiles).
 template <int D, bool TAIL, bool RAGGED, int KOFF, int VOFF>
 __device__ inline void absorb_tile(State<D>& st, const bf16x8 (&qreg)[D / 16], const LaneCtx& lc,
@@ -457,7 +505,9 @@ __device__ inline void absorb_tile(State<D>& st, const bf16x8 (&qreg)[D / 16], c
 // LDS map of the staging area (byte offsets): K stages | V stages; Phase 2 reuses it as
 // centroid keys (K stage 0) and centroid values (V stage 0).
 // Three workgroups per CU at head_dim 64 (168 VGPRs, 33 KB LDS each), two at 128.
-template <int D, bool DENSE>
+// TPB: 64-key tiles per block of the selection (1: block 64, two query blocks per workgroup;
+// 2: block 128, one); the dense kernel is built with TPB = 2 (it has no block lists).
+template <int D, bool DENSE, int TPB>
 __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void attn_bf16_kernel(PB p) {
   constexpr int ROWB = Geo<D>::ROWB, TILEB = Geo<D>::TILEB, NKS = Geo<D>::NKS, NDT = Geo<D>::NDT;
   constexpr int CPR = Geo<D>::CPR, RPL = Geo<D>::RPL;
@@ -465,6 +515,9 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void attn_bf16_kernel(PB p) {
   __shared__ __attribute__((aligned(1024))) unsigned char stage[4 * TILEB];   // K0 | K1 | V0 | V1
   __shared__ unsigned int chosen[2][MASK_WORDS];
   __shared__ __attribute__((aligned(16))) float bias_s[2][kTile];
+  __shared__ unsigned short trip_list[DENSE || TPB == 2 ? 2 : kMaxBlocks + 2];          // Phase-1 walk of a block-64 workgroup
+  __shared__ unsigned short pre_s[DENSE || TPB == 2 ? 1 : MASK_WORDS + 1], pre_a[DENSE || TPB == 2 ? 1 : MASK_WORDS + 1],
+      pre_b[DENSE || TPB == 2 ? 1 : MASK_WORDS + 1];                                   // tiles below each mask word, by class
 
   // Workgroup ids are dealt round-robin to the 8 XCDs.  Dense attention gives each XCD a
   // contiguous range of (head, query tile) items, so one XCD's L2 serves one head whose tiles
@@ -491,7 +544,7 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void attn_bf16_kernel(PB p) {
   const int L = p.L, N = p.N;
   const unsigned char* kg = reinterpret_cast<const unsigned char*>(p.k + bh * (size_t)L * D);
   const unsigned char* vg = reinterpret_cast<const unsigned char*>(p.v + bh * (size_t)L * D);
-  const int tpb = p.B / kTile;                       // tiles per block: 1 or 2
+  constexpr int tpb = TPB;                           // tiles per block: 1 or 2
   const int qb = tpb == 1 ? (wave >> 1) : 0;         // which of the workgroup's query blocks
   const float c = p.scale * 1.44269504088896340736f;
   LDS_PTR(unsigned char) lds = (LDS_PTR(unsigned char)) & stage[0];
@@ -553,118 +606,246 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void attn_bf16_kernel(PB p) {
     __syncthreads();
   }
 
-  // ---- Phase 1: walk the exact tiles (all tiles; or the union of the selected blocks) ----
-  // The main loop takes full tiles only; a ragged last tile is folded in afterwards.
+  // ---- Phase 1: the walk over full exact tiles (a ragged last tile is folded in afterwards) ----
   const int n_tiles = L / kTile;
-  int w_word = -1, pend = -1, pend_in = 0, dense_t = 0;
-  unsigned int w_union = 0u, w_m0 = 0u, w_m1 = 0u;
-  auto next_tile = [&](int& tile, int& inmask) -> bool {
+  constexpr int HALFB = TILEB / 2;
+
+  // Block 64, PISA: the two query blocks' lists are merged into one trip list in LDS.  A tile
+  // both blocks selected becomes one full trip in which every wave takes all 64 keys.  The
+  // tiles only the first block selected and those only the second selected are paired up in
+  // ascending order (i-th with i-th; both blocks hold k entries, so the two sets are equally
+  // long unless an entry was out of range or the ragged tile is in one list only).  A pair
+  // becomes two split trips, one per 32-key half of the two tiles: stage rows 0..31 hold the
+  // half of the first block's tile, rows 32..63 the half of the second block's, and each
+  // block's waves take the 32 keys that are theirs, so no wave sits a trip out.  Entries are
+  // ordered by tile index, a pair by the larger of its two, so the walk stays ascending; tiles
+  // left without a partner follow at the end as split trips with one block idle.
+  // Entry: bits 0..12 tile, bits 13..15 kind (0 shared, 1 member of a pair: first-block tile
+  // then second-block tile, 2 / 3 unpaired tile of the first / second block).
+  int n_entries = 0;
+  if (!DENSE && TPB == 1) {
+    // scratch inside the (still unused) staging area
+    LDS_PTR(unsigned int) w_s = (LDS_PTR(unsigned int))(lds);                       // [128] shared words
+    LDS_PTR(unsigned int) w_a = w_s + MASK_WORDS;                                    // first block only
+    LDS_PTR(unsigned int) w_b = w_a + MASK_WORDS;                                    // second block only
+    LDS_PTR(unsigned short) l_s = (LDS_PTR(unsigned short))(w_b + MASK_WORDS);       // [4096] compacted
+    LDS_PTR(unsigned short) l_a = l_s + kMaxBlocks;
+    LDS_PTR(unsigned short) l_b = l_a + kMaxBlocks;
+    static_assert(3 * MASK_WORDS * 4 + 3 * kMaxBlocks * 2 <= 4 * Geo<64>::TILEB, "list scratch must fit the staging area");
+    if (wave == 0) {
+      // lane l owns mask words 2l, 2l + 1: split them, count, exclusive scan over the lanes
+      unsigned ws[2], wa[2], wb[2];
+      unsigned cs = 0, cab = 0, cs0 = 0, cab0 = 0;
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int w = 2 * lane + u;
+        unsigned c0 = 0u, c1 = 0u;
+        if (w < nwords) {
+          const int first = 32 * w;                      // tiles >= n_tiles (the ragged one) stay out
+          const unsigned lim = first + 32 <= n_tiles ? 0xffffffffu
+                               : (first >= n_tiles ? 0u : ((1u << (n_tiles - first)) - 1u));
+          c0 = chosen[0][w] & lim;
+          c1 = chosen[1][w] & lim;
+        }
+        ws[u] = c0 & c1;
+        wa[u] = c0 & ~c1;
+        wb[u] = c1 & ~c0;
+        w_s[w] = ws[u];
+        w_a[w] = wa[u];
+        w_b[w] = wb[u];
+        if (u == 0) {
+          cs0 = __builtin_popcount(ws[0]);
+          cab0 = __builtin_popcount(wa[0]) | (__builtin_popcount(wb[0]) << 16);
+        }
+        cs += __builtin_popcount(ws[u]);
+        cab += __builtin_popcount(wa[u]) | (__builtin_popcount(wb[u]) << 16);
+      }
+      unsigned is = cs, iab = cab;                       // inclusive scans (counts <= 4096: 16-bit halves never carry)
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const unsigned ts = __shfl_up(is, off), tab = __shfl_up(iab, off);
+        if (lane >= off) {
+          is += ts;
+          iab += tab;
+        }
+      }
+      const unsigned es = is - cs, eab = iab - cab;      // exclusive prefix of this lane's first word
+      pre_s[2 * lane] = (unsigned short)es;
+      pre_s[2 * lane + 1] = (unsigned short)(es + cs0);
+      pre_a[2 * lane] = (unsigned short)(eab & 0xffffu);
+      pre_a[2 * lane + 1] = (unsigned short)((eab + cab0) & 0xffffu);
+      pre_b[2 * lane] = (unsigned short)(eab >> 16);
+      pre_b[2 * lane + 1] = (unsigned short)((eab + cab0) >> 16);
+      if (lane == 63) {
+        pre_s[MASK_WORDS] = (unsigned short)is;
+        pre_a[MASK_WORDS] = (unsigned short)(iab & 0xffffu);
+        pre_b[MASK_WORDS] = (unsigned short)(iab >> 16);
+      }
+      // compaction: this lane's tiles, ascending, at their ranks
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int w = 2 * lane + u;
+        unsigned rs = u == 0 ? es : es + cs0;
+        unsigned ra = (u == 0 ? eab : eab + cab0) & 0xffffu;
+        unsigned rb = (u == 0 ? eab : eab + cab0) >> 16;
+        for (unsigned m = ws[u]; m; m &= m - 1u) l_s[rs++] = (unsigned short)(32 * w + __builtin_ctz(m));
+        for (unsigned m = wa[u]; m; m &= m - 1u) l_a[ra++] = (unsigned short)(32 * w + __builtin_ctz(m));
+        for (unsigned m = wb[u]; m; m &= m - 1u) l_b[rb++] = (unsigned short)(32 * w + __builtin_ctz(m));
+      }
+    }
+    __syncthreads();
+    const int n_s = pre_s[MASK_WORDS], n_a = pre_a[MASK_WORDS], n_b = pre_b[MASK_WORDS];
+    const int n_pairs = min(n_a, n_b);
+    for (int i = tid; i < n_pairs; i += 256) {           // pair i sits behind the shared tiles below its larger member
+      const int ta = l_a[i], tb = l_b[i];
+      const int key = max(ta, tb);
+      const int below = pre_s[key >> 5] + __builtin_popcount(w_s[key >> 5] & ((1u << (key & 31)) - 1u));
+      trip_list[2 * i + below] = (unsigned short)(ta | (1 << 13));
+      trip_list[2 * i + below + 1] = (unsigned short)(tb | (1 << 13));
+    }
+    for (int m = tid; m < n_s; m += 256) {               // shared tile m sits behind the pairs that lie wholly below it
+      const int t = l_s[m];
+      const unsigned low = (1u << (t & 31)) - 1u;
+      const int na = pre_a[t >> 5] + __builtin_popcount(w_a[t >> 5] & low);
+      const int nb = pre_b[t >> 5] + __builtin_popcount(w_b[t >> 5] & low);
+      trip_list[m + 2 * min(na, nb)] = (unsigned short)t;
+    }
+    const int base = n_s + 2 * n_pairs;
+    for (int i = n_pairs + tid; i < n_a; i += 256) trip_list[base + i - n_pairs] = (unsigned short)(l_a[i] | (2 << 13));
+    for (int i = n_pairs + tid; i < n_b; i += 256) trip_list[base + i - n_pairs] = (unsigned short)(l_b[i] | (3 << 13));
+    n_entries = __builtin_amdgcn_readfirstlane(base + (n_a - n_pairs) + (n_b - n_pairs));
+    if (tid < 2) trip_list[n_entries + tid] = 0;
+    __syncthreads();                                     // list complete; the staging area is free again
+  }
+
+  // The trip generator (wave-uniform state in scalar registers).  A trip is handed around as
+  // three plain integers: lo, hi (see Trip) and a work mask wm, in which bit 2 b + e says that
+  // the waves of query block b take stage half e (keys 32 e .. 32 e + 31).
+  int li = 0, split_left = 0, split_lo = 0, split_hi = 0, split_wm = 0, w_word = -1, pend = -1, dense_t = 0;
+  unsigned int w_bits = 0u;
+  auto next_trip = [&](int& lo, int& hi, int& wm) -> bool {
     if (DENSE) {
       if (dense_t >= n_tiles) return false;
-      tile = dense_t++;
-      inmask = 3;
+      lo = dense_t * TILEB;
+      hi = lo + HALFB;
+      wm = 15;
+      ++dense_t;
       return true;
     }
-    if (pend >= 0) {
-      tile = pend;
-      inmask = pend_in;
-      pend = -1;
-      return true;
-    }
-    while (w_union == 0u) {
-      if (++w_word >= nwords) return false;
-      w_m0 = __builtin_amdgcn_readfirstlane(chosen[0][w_word]);
-      w_m1 = __builtin_amdgcn_readfirstlane(chosen[1][w_word]);
-      w_union = w_m0 | w_m1;
-    }
-    const int b = __builtin_ctz(w_union);
-    w_union &= w_union - 1u;
-    const int j = w_word * 32 + b;
-    inmask = ((w_m0 >> b) & 1u) | (((w_m1 >> b) & 1u) << 1);
-    if (tpb == 1) {
-      tile = j;
-      if (tile >= n_tiles) return false;       // only the ragged tile is left
-    } else {
-      tile = 2 * j;
-      inmask = 3;
-      if (tile >= n_tiles) return false;
-      if (2 * j + 1 < n_tiles) {
-        pend = 2 * j + 1;
-        pend_in = 3;
+    if (TPB == 2) {                                      // one 128-token block per workgroup: two tiles per entry
+      int tile;
+      if (pend >= 0) {
+        tile = pend;
+        pend = -1;
+      } else {
+        while (w_bits == 0u) {
+          if (++w_word >= nwords) return false;
+          w_bits = __builtin_amdgcn_readfirstlane(chosen[0][w_word]);
+        }
+        const int j = w_word * 32 + __builtin_ctz(w_bits);
+        w_bits &= w_bits - 1u;
+        tile = 2 * j;
+        if (tile >= n_tiles) return false;               // only the ragged tile is left
+        if (tile + 1 < n_tiles) pend = tile + 1;
       }
+      lo = tile * TILEB;
+      hi = lo + HALFB;
+      wm = 15;
+      return true;
     }
+    if (split_left) {                                    // second half of a split pair
+      lo = split_lo;
+      hi = split_hi;
+      wm = split_wm;
+      split_left = 0;
+      return true;
+    }
+    if (li >= n_entries) return false;
+    const unsigned e0 = __builtin_amdgcn_readfirstlane((unsigned)trip_list[li]);
+    const unsigned e1 = __builtin_amdgcn_readfirstlane((unsigned)trip_list[li + 1]);
+    const int kind = e0 >> 13, tile = e0 & 0x1fff;
+    if (kind == 0) {
+      ++li;
+      lo = tile * TILEB;
+      hi = lo + HALFB;
+      wm = 15;
+      return true;
+    }
+    const int tb = kind == 1 ? (int)(e1 & 0x1fff) : tile;
+    li += kind == 1 ? 2 : 1;
+    lo = tile * TILEB;                                   // first block's tile  -> stage rows 0..31
+    hi = tb * TILEB;                                     // second block's tile -> stage rows 32..63
+    wm = kind == 1 ? 9 : (kind == 2 ? 1 : 8);            // first block: half 0; second block: half 1
+    split_lo = lo + HALFB;
+    split_hi = hi + HALFB;
+    split_wm = wm;
+    split_left = 1;
     return true;
   };
-  auto issue_k = [&](int tile, int koff) {
-    load_tile_async<D, true>(lc, kg + (size_t)tile * TILEB, L - tile * kTile, lds_addr + koff);
-  };
-  auto issue_v = [&](int tile, int voff) {
-    load_tile_async<D, false>(lc, vg + (size_t)tile * TILEB, L - tile * kTile, lds_addr + voff);
-  };
 
-  // Software pipeline over tiles t = 0, 1, ...: K runs one tile ahead of V.  In trip t the
-  // wave issues S^T(t+1) on the matrix cores while the vector ALUs work through the softmax
-  // of tile t (the two are independent), then O^T += V(t)^T P(t)^T.  One barrier per trip:
-  // after it K(t+1) and V(t) have landed and K stage t&1 / V stage (t+1)&1 are free, so the
-  // loads of K(t+2) and V(t+1) go out during the trip, between the MFMAs of S^T(t+1) (a wave
-  // of a block that skips the tile issues its share up front).
-  int t0 = 0, in0 = 0, t1 = 0, in1 = 0, t2 = 0, in2 = 0;
-  bool have0 = next_tile(t0, in0);
+  // Software pipeline over trips t = 0, 1, ...: K runs one trip ahead of V.  One barrier per
+  // trip; after it K(t+1) and V(t) have landed and K stage t&1 / V stage (t+1)&1 are free, so
+  // the loads of K(t+2) and V(t+1) go out.  The wave then runs the softmax of trip t,
+  // O^T += V(t)^T P(t)^T, and last S^T(t+1), which takes over the score registers the softmax
+  // has just consumed.  Where trips can be split (block 64, PISA) every step comes in two halves
+  // of 32 keys, each guarded by its bit of the trip's work mask (both set in a full trip).
+  constexpr bool SPLITS = !DENSE && TPB == 1;
+  const int my_shift = (int)(lc.wave >> 1) * 2;
+  int lo0 = 0, hi0 = 0, wm0 = 0, lo1 = 0, hi1 = 0, wm1 = 0, lo2 = 0, hi2 = 0, wm2 = 0;
+  bool have0 = next_trip(lo0, hi0, wm0);
   bool have1 = false, have2 = false;
-  f32x16 sc0, sc1;                       // S^T of the current tile
+  f32x16 sc0, sc1;                       // S^T of the current trip: stage rows 0..31 / 32..63
+  auto scores = [&](auto koff_tag, int wm) {
+    constexpr int KOFF = decltype(koff_tag)::value;
+    if (!SPLITS) {
+      qk_tile<D, KOFF>(sc0, sc1, qreg, lc);
+    } else {
+      if ((wm >> my_shift) & 1) qk_rows<D, KOFF, 0>(sc0, qreg, lc);
+      if ((wm >> my_shift) & 2) qk_rows<D, KOFF, 32>(sc1, qreg, lc);
+    }
+  };
   if (have0) {
-    issue_k(t0, KST0);
-    have1 = next_tile(t1, in1);
+    load_stage<D, true>(lc, kg, Trip{lo0, hi0}, lds_addr + KST0);
+    have1 = next_trip(lo1, hi1, wm1);
     wait_async_loads();
     __syncthreads();
-    if (have1) issue_k(t1, KST1);
-    issue_v(t0, VST0);
-    if ((in0 >> qb) & 1) qk_tile<D, KST0>(sc0, sc1, qreg, lc);
+    if (have1) load_stage<D, true>(lc, kg, Trip{lo1, hi1}, lds_addr + KST1);
+    load_stage<D, false>(lc, vg, Trip{lo0, hi0}, lds_addr + VST0);
+    scores(std::integral_constant<int, KST0>{}, wm0);
   }
   auto trip = [&](auto parity_tag) {
-    constexpr int P = decltype(parity_tag)::value;       // parity of the current tile
+    constexpr int P = decltype(parity_tag)::value;       // parity of the current trip
     constexpr int K_NEXT = P ? KST0 : KST1, K_FREE = P ? KST1 : KST0;
     constexpr int V_CUR = P ? VST1 : VST0, V_FREE = P ? VST0 : VST1;
-    have2 = have1 && next_tile(t2, in2);
+    have2 = have1 && next_trip(lo2, hi2, wm2);
     wait_async_loads();
     __syncthreads();
-    const bool do_cur = (in0 >> qb) & 1;
-    const bool do_next = have1 && ((in1 >> qb) & 1);
-    // Past the end of the walk the loads repeat tile t0 into the free stages (harmless).
-    const int tk = have2 ? t2 : t0, tv = have1 ? t1 : t0;
-    if (do_cur && do_next) {
-      f32x16 sn0, sn1;
+    // Past the end of the walk the loads repeat trip 0's sources into the free stages (harmless).
+    load_stage<D, true>(lc, kg, Trip{have2 ? lo2 : lo0, have2 ? hi2 : hi0}, lds_addr + K_FREE);
+    load_stage<D, false>(lc, vg, Trip{have1 ? lo1 : lo0, have1 ? hi1 : hi0}, lds_addr + V_FREE);
+    const bool do_lo = !SPLITS || ((wm0 >> my_shift) & 1), do_hi = !SPLITS || ((wm0 >> my_shift) & 2);
+    if (do_lo || do_hi) {
       bf16x8 pb[4];
-      // straight-line: S^T(t+1) on the matrix cores, exp / sum / pack of tile t on the VALU
-      qk_tile_dma<D, K_NEXT>(sn0, sn1, qreg, lc, kg + (size_t)tk * TILEB, lds_addr + K_FREE,
-                          vg + (size_t)tv * TILEB, lds_addr + V_FREE);
-      float psum = softmax_exp_stale(st, sc0, sc1, pb, c);
-      if (__any(!(psum < kStaleLimit))) {          // first tile of this wave, or a maximum that ran away
-        softmax_max<D, false>(st, sc0, sc1, lc, nullptr, c);
-        psum = softmax_exp_stale(st, sc0, sc1, pb, c);
+      float nm = -st.m, pa = 0.f, pc = 0.f;
+      if (do_lo) exp_rows(sc0, c, nm, pb[0], pb[1], pa, pc);
+      if (do_hi) exp_rows(sc1, c, nm, pb[2], pb[3], pa, pc);
+      if (__any(!(pa + pc < kStaleLimit))) {         // first keys of this wave, or a maximum that ran away
+        float t = -INFINITY;
+        if (do_lo) t = max_rows(sc0);
+        if (do_hi) t = fmaxf(t, max_rows(sc1));
+        raise_max<D>(st, t * c);
+        nm = -st.m;
+        pa = pc = 0.f;
+        if (do_lo) exp_rows(sc0, c, nm, pb[0], pb[1], pa, pc);
+        if (do_hi) exp_rows(sc1, c, nm, pb[2], pb[3], pa, pc);
       }
-      st.l += psum;
-      pv_tile<D, V_CUR>(st, pb, lc);
-      sc0 = sn0;
-      sc1 = sn1;
-    } else if (do_cur) {
-      issue_k(tk, K_FREE);
-      issue_v(tv, V_FREE);
-      bf16x8 pb[4];
-      float psum = softmax_exp_stale(st, sc0, sc1, pb, c);
-      if (__any(!(psum < kStaleLimit))) {
-        softmax_max<D, false>(st, sc0, sc1, lc, nullptr, c);
-        psum = softmax_exp_stale(st, sc0, sc1, pb, c);
-      }
-      st.l += psum;
-      pv_tile<D, V_CUR>(st, pb, lc);
-    } else {
-      issue_k(tk, K_FREE);
-      issue_v(tv, V_FREE);
-      if (do_next) qk_tile<D, K_NEXT>(sc0, sc1, qreg, lc);
+      st.l += pa + pc;
+      if (do_lo) pv_rows<D, V_CUR, 0>(st, pb[0], pb[1], lc);
+      if (do_hi) pv_rows<D, V_CUR, 32>(st, pb[2], pb[3], lc);
     }
-    t0 = t1; in0 = in1; have0 = have1;
-    t1 = t2; in1 = in2; have1 = have2;
+    if (have1) scores(std::integral_constant<int, K_NEXT>{}, wm1);
+    lo0 = lo1; hi0 = hi1; wm0 = wm1; have0 = have1;
+    lo1 = lo2; hi1 = hi2; wm1 = wm2; have1 = have2;
   };
   while (have0) {
     trip(std::integral_constant<int, 0>{});
@@ -681,8 +862,8 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void attn_bf16_kernel(PB p) {
                                   (tpb == 1 ? (((chosen[1][jb >> 5] >> (jb & 31)) & 1u) << 1) : 0u));
     if (inm) {            // uniform over the workgroup
       __syncthreads();
-      issue_k(tile, KST0);
-      issue_v(tile, VST0);
+      load_tile_async<D, true>(lc, kg + (size_t)tile * TILEB, L - tile * kTile, lds_addr + KST0);
+      load_tile_async<D, false>(lc, vg + (size_t)tile * TILEB, L - tile * kTile, lds_addr + VST0);
       wait_async_loads();
       __syncthreads();
       if ((inm >> qb) & 1)
@@ -782,7 +963,7 @@ static hipError_t launch_attention_bf16_d(const Dims& dm, const AttnArgs& a, hip
   p.first_order = a.hsum != nullptr;
   const int grid = ((p.total + 63) / 64) * 64;
   if (a.dense) {
-    hipLaunchKernelGGL((attn_bf16_kernel<D, true>), dim3(grid), dim3(256), 0, stream, p);
+    hipLaunchKernelGGL((attn_bf16_kernel<D, true, 2>), dim3(grid), dim3(256), 0, stream, p);
     return hipGetLastError();
   }
   if (a.k_top < dm.N && a.kbar) {
@@ -802,7 +983,8 @@ static hipError_t launch_attention_bf16_d(const Dims& dm, const AttnArgs& a, hip
     p.hpack = hpack;
     p.bias = bias;
   }
-  hipLaunchKernelGGL((attn_bf16_kernel<D, false>), dim3(grid), dim3(256), 0, stream, p);
+  if (dm.B == kTile) hipLaunchKernelGGL((attn_bf16_kernel<D, false, 1>), dim3(grid), dim3(256), 0, stream, p);
+  else hipLaunchKernelGGL((attn_bf16_kernel<D, false, 2>), dim3(grid), dim3(256), 0, stream, p);
   return hipGetLastError();
 }
 
