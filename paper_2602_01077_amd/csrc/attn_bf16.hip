@@ -514,7 +514,7 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void attn_bf16_kernel(PB p) {
   constexpr int KST0 = 0, KST1 = TILEB, VST0 = 2 * TILEB, VST1 = 3 * TILEB;
   __shared__ __attribute__((aligned(1024))) unsigned char stage[4 * TILEB];   // K0 | K1 | V0 | V1
   __shared__ unsigned int chosen[2][MASK_WORDS];
-  __shared__ __attribute__((aligned(16))) float bias_s[2][kTile];
+  __shared__ __attribute__((aligned(16))) float bias_s[2][2][kTile];          // [stage parity][query block][centroid]
   __shared__ unsigned short trip_list[DENSE || TPB == 2 ? 2 : kMaxBlocks + 2];          // Phase-1 walk of a block-64 workgroup
   __shared__ unsigned short pre_s[DENSE || TPB == 2 ? 1 : MASK_WORDS + 1], pre_a[DENSE || TPB == 2 ? 1 : MASK_WORDS + 1],
       pre_b[DENSE || TPB == 2 ? 1 : MASK_WORDS + 1];                                   // tiles below each mask word, by class
@@ -876,20 +876,31 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void attn_bf16_kernel(PB p) {
   if (approx) {
     const unsigned char* kcg = reinterpret_cast<const unsigned char*>(p.kcen + bh * (size_t)p.npad * D);
     const unsigned char* vbg = reinterpret_cast<const unsigned char*>(p.vbar + bh * (size_t)p.npad * D);
-    LDS_PTR(const float) my_bias = (LDS_PTR(const float)) & bias_s[qb][0];
-    for (int g0 = 0; g0 < N; g0 += kTile) {
-      __syncthreads();                         // previous tile fully consumed
-      load_tile_async<D, true>(lc, kcg + (size_t)g0 * ROWB, kTile, lds_addr + KST0);
-      load_tile_async<D, false>(lc, vbg + (size_t)g0 * ROWB, kTile, lds_addr + VST0);
+    // Double buffered: tile g + 1 (and its bias vector) is fetched while tile g is absorbed.
+    auto fetch = [&](int g0, auto parity_tag) {
+      constexpr int P = decltype(parity_tag)::value;
+      load_tile_async<D, true>(lc, kcg + (size_t)g0 * ROWB, kTile, lds_addr + (P ? KST1 : KST0));
+      load_tile_async<D, false>(lc, vbg + (size_t)g0 * ROWB, kTile, lds_addr + (P ? VST1 : VST0));
       if (tid < 2 * kTile) {
         const int b = tid >> 6, j = g0 + (tid & 63);
         const bool masked =
             (tpb == 2 && b == 1) ? true : ((chosen[b][(j >> 5) & (MASK_WORDS - 1)] >> (j & 31)) & 1u);
-        bias_s[b][tid & 63] = masked ? -INFINITY : p.bias[j];
+        bias_s[P][b][tid & 63] = masked ? -INFINITY : p.bias[j];
       }
+    };
+    auto absorb = [&](int g0, auto parity_tag) {
+      constexpr int P = decltype(parity_tag)::value;
       wait_async_loads();
-      __syncthreads();
-      absorb_tile<D, true, false, KST0, VST0>(st, qreg, lc, my_bias, kTile, c);
+      __syncthreads();                         // tile g has landed; tile g - 1 is fully consumed
+      if (g0 + kTile < N) fetch(g0 + kTile, std::integral_constant<int, 1 - P>{});
+      absorb_tile<D, true, false, (P ? KST1 : KST0), (P ? VST1 : VST0)>(
+          st, qreg, lc, (LDS_PTR(const float)) & bias_s[P][qb][0], kTile, c);
+    };
+    __syncthreads();                           // the stages are free (Phase 1 and the ragged tile are done)
+    fetch(0, std::integral_constant<int, 0>{});
+    for (int g0 = 0; g0 < N; g0 += 2 * kTile) {
+      absorb(g0, std::integral_constant<int, 0>{});
+      if (g0 + kTile < N) absorb(g0 + kTile, std::integral_constant<int, 1>{});
     }
   }
 
