@@ -103,6 +103,8 @@ def main():
     ap.add_argument("--no-probe", action="store_true", help="skip the measured-peak probes (MFMA loop, 1 GiB copy)")
     ap.add_argument("--covariance-aware", choices=["spectral", "frobenius"], default=None,
                     help="add the covariance-aware selection score (pisa_block_heterogeneity) to the step")
+    ap.add_argument("--hbar-from-stats", action="store_true",
+                    help="covariance-aware selection takes Hbar from the statistics' fp32 hsum (saves one fp64 pass)")
     ap.add_argument("--copy-calibration", type=int, default=0,
                     help="also run this many plain device copies of 1 GiB (reference for rocprofv3 --pmc byte counters)")
     ap.add_argument("--traffic-json", default=None,
@@ -156,7 +158,8 @@ def main():
             events[1].record()
         log_m = None
         if norm is not None:       # counted in the select stage
-            log_m = pisa.block_heterogeneity(shape, k, v, stats["kbar64"], norm, 1e-6, ws)
+            log_m = pisa.block_heterogeneity(shape, k, v, stats["kbar64"], norm, 1e-6, ws,
+                                             hsum=stats["hsum"] if args.hbar_from_stats else None)
         pisa.select_into(shape, stats["qbar64"], stats["kbar64"], k_top, idx, gap, ws, log_m)
         if events:
             events[2].record()

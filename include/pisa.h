@@ -98,18 +98,25 @@ int32_t pisa_block_stats(const pisa_shape* shape, const void* q, const void* k, 
  * Methodology, "Covariance-Aware Block Selection": per key block j the heterogeneity
  *   M_j = || H_j - Hbar ||,  H_j = sum_n (k_{j,n} - kbar_j)^T v_{j,n},  Hbar = (1/N) sum_j H_j,
  * and the column bias log(M_j + eps) that the selection score adds to the pooled logit.
- *   norm_kind  PISA_NORM_SPECTRAL: operator 2-norm (the norm of the paper's error analysis),
- *              by 48 power-iteration steps on (H_j - Hbar)^T (H_j - Hbar) from a fixed start
- *              vector: a lower bound that, for the nearly flat spectra of these rank-<=B
- *              matrices, can stop a few percent short of the exact value;
+ *   norm_kind  PISA_NORM_SPECTRAL: operator 2-norm (the norm of the paper's error analysis):
+ *              the largest eigenvalue theta of (H_j - Hbar)^T (H_j - Hbar) by a Krylov-type
+ *              iteration from a fixed start vector, run until the residual of the eigenpair is
+ *              below 1e-7 theta (at most 300 steps), M_j = sqrt(theta): within 5e-8 relative of a
+ *              singular value by construction, in practice equal to the largest one to rounding;
  *              PISA_NORM_FROBENIUS: exact (fp64), cheaper, an upper bound of the spectral norm.
  *   kbar64     fp64 [batch,heads,N,d] as written by pisa_block_stats
+ *   hsum       NULL: Hbar is accumulated here in fp64 (one more pass over K and V), and M_j matches
+ *              a plain fp64 evaluation to rounding.  Or fp32 [batch,heads,d,d] as written by
+ *              pisa_block_stats: Hbar = hsum / N is taken from it, which saves that pass; Hbar then
+ *              carries the fp32 rounding of hsum (about 1e-6 of its largest entry), and M_j an
+ *              error of about 1e-7 relative, since ||Hbar|| is a fraction of ||H_j - Hbar||.
  *   log_m      fp64 [batch,heads,N], written
  * All arithmetic is fp64.  `workspace` must hold pisa_workspace_bytes(shape).
  * The paper enables this score for image models only; pass log_m as `col_bias` to pisa_select.
  */
 int32_t pisa_block_heterogeneity(const pisa_shape* shape, const void* k, const void* v,
-                                 const double* kbar64, int32_t norm_kind, double eps, double* log_m,
+                                 const double* kbar64, const float* hsum, int32_t norm_kind, double eps,
+                                 double* log_m,
                                  void* workspace, size_t workspace_bytes, void* stream);
 
 /*

@@ -56,7 +56,7 @@ def _load() -> ctypes.CDLL:
     lib.pisa_workspace_bytes.restype = sz
     lib.pisa_block_stats.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.pisa_block_stats.restype = i32
-    lib.pisa_block_heterogeneity.argtypes = [shp, vp, vp, vp, i32, ctypes.c_double, vp, vp, sz, vp]
+    lib.pisa_block_heterogeneity.argtypes = [shp, vp, vp, vp, vp, i32, ctypes.c_double, vp, vp, sz, vp]
     lib.pisa_block_heterogeneity.restype = i32
     lib.pisa_select.argtypes = [shp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
     lib.pisa_select.restype = i32
@@ -176,14 +176,16 @@ def block_stats_into(shape, q, k, v, out: dict, workspace: torch.Tensor) -> None
 
 
 def block_heterogeneity(shape: PisaShape, k, v, kbar64, norm: int = PISA_NORM_SPECTRAL, eps: float = 1e-6,
-                        workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """pisa_block_heterogeneity.  Returns log(M_j + eps), fp64 [b,h,N]."""
+                        workspace: Optional[torch.Tensor] = None, hsum: Optional[torch.Tensor] = None
+                        ) -> torch.Tensor:
+    """pisa_block_heterogeneity.  Returns log(M_j + eps), fp64 [b,h,N].  hsum (fp32, from
+    block_stats) lets the library take Hbar from it instead of accumulating it again in fp64."""
     b, h, n, _ = kbar64.shape
     log_m = torch.empty(b, h, n, dtype=torch.float64, device=k.device)
     ws = alloc_workspace(shape, k.device) if workspace is None else workspace
     _check(_lib.pisa_block_heterogeneity(
         ctypes.byref(shape), _dev(k, "k"), _dev(v, "v", like=k), _dev(kbar64, "kbar64", torch.float64),
-        norm, float(eps), _dev(log_m, "log_m", torch.float64),
+        _dev(hsum, "hsum", torch.float32), norm, float(eps), _dev(log_m, "log_m", torch.float64),
         _dev(ws, "workspace"), ws.numel() * ws.element_size(), _stream()))
     return log_m
 
@@ -280,19 +282,21 @@ def probe_shader_clock(window_ms: float, counts: torch.Tensor) -> float:
 
 def pisa_forward(q, k, v, block: int = 64, sparsity: float = 0.85, first_order: bool = True,
                  want_lse: bool = False, approximate: bool = True, covariance_aware: bool = False,
-                 norm: int = PISA_NORM_SPECTRAL, eps: float = 1e-6, scale: Optional[float] = None):
+                 norm: int = PISA_NORM_SPECTRAL, eps: float = 1e-6, scale: Optional[float] = None,
+                 hbar_from_stats: bool = False):
     """The whole hot path: block_stats -> select -> attention.
 
     first_order=False gives the zeroth-order variant, approximate=False plain block-sparse
     attention over the selected blocks, covariance_aware=True adds log(M_j + eps) to the
-    selection score.  Returns dict(out, lse, idx, kth_gap, stats, k_top, log_m).
+    selection score (hbar_from_stats=True: with Hbar from the statistics' fp32 hsum).  Returns dict(out, lse, idx, kth_gap, stats, k_top, log_m).
     """
     shape = make_shape(q, block, scale)
     n = num_blocks(q.shape[2], block)
     k_top = topk_count(n, sparsity)
     ws = alloc_workspace(shape, q.device)
     stats = block_stats(q, k, v, block, ws)
-    log_m = block_heterogeneity(shape, k, v, stats["kbar64"], norm, eps, ws) if covariance_aware else None
+    log_m = block_heterogeneity(shape, k, v, stats["kbar64"], norm, eps, ws,
+                                hsum=stats["hsum"] if hbar_from_stats else None) if covariance_aware else None
     idx, gap = select(shape, stats["qbar64"], stats["kbar64"], k_top, ws, col_bias=log_m)
     out, lse = attention(shape, q, k, v, stats["kbar"] if approximate else None,
                          stats["vsum"] if approximate else None,

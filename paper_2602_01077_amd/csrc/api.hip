@@ -136,7 +136,8 @@ int32_t pisa_block_stats(const pisa_shape* shape, const void* q, const void* k, 
 }
 
 int32_t pisa_block_heterogeneity(const pisa_shape* shape, const void* k, const void* v,
-                                 const double* kbar64, int32_t norm_kind, double eps, double* log_m,
+                                 const double* kbar64, const float* hsum, int32_t norm_kind, double eps,
+                                 double* log_m,
                                  void* workspace, size_t workspace_bytes, void* stream) {
   Dims dm;
   int32_t rc = resolve(shape, &dm);
@@ -145,13 +146,13 @@ int32_t pisa_block_heterogeneity(const pisa_shape* shape, const void* k, const v
   if (norm_kind != PISA_NORM_SPECTRAL && norm_kind != PISA_NORM_FROBENIUS)
     return fail(PISA_INVALID_ARG, "norm_kind must be PISA_NORM_SPECTRAL (0) or PISA_NORM_FROBENIUS (1)");
   if (!(eps >= 0.0)) return fail(PISA_INVALID_ARG, "eps must be >= 0");
-  PISA_CHECK_ALIGN(k, v, kbar64, log_m, workspace);
+  PISA_CHECK_ALIGN(k, v, kbar64, hsum, log_m, workspace);
   size_t need = hetero_workspace_bytes(dm);
   if (!workspace) return fail(PISA_INVALID_ARG, "workspace is NULL (need %zu bytes)", need);
   if (workspace_bytes < need)
     return fail(PISA_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, need %zu", workspace_bytes, need);
-  hipError_t e = launch_block_heterogeneity(dm, k, v, kbar64, norm_kind == PISA_NORM_SPECTRAL,
-                                            kPowerIterations, eps, log_m, (double*)workspace,
+  hipError_t e = launch_block_heterogeneity(dm, k, v, kbar64, hsum, norm_kind == PISA_NORM_SPECTRAL,
+                                            kSpectralMaxSteps, eps, log_m, (double*)workspace,
                                             (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail("pisa_block_heterogeneity", e);
   return PISA_OK;

@@ -22,8 +22,10 @@ struct Dims {
 constexpr int kTile = 64;
 // Largest block count the selection and the Phase-2 column mask are sized for.
 constexpr int kMaxBlocks = 4096;
-// Power-iteration steps (on D^T D) for the spectral norm of the block heterogeneity.
-constexpr int kPowerIterations = 48;
+// Spectral norm of the block heterogeneity: the eigenvalue iteration on D^T D stops at this
+// relative residual (||A x - theta x|| <= kRelResidual * theta), or after kSpectralMaxSteps steps.
+constexpr double kRelResidual = 1e-7;
+constexpr int kSpectralMaxSteps = 300;
 
 // Records the message returned by pisa_last_error() and returns `code`.
 int32_t fail(int32_t code, const char* fmt, ...);
@@ -48,7 +50,7 @@ hipError_t launch_select(const Dims& dm, const double* qbar64, const double* kba
                          hipStream_t stream);
 size_t hetero_workspace_bytes(const Dims& dm);
 hipError_t launch_block_heterogeneity(const Dims& dm, const void* k, const void* v, const double* kbar64,
-                                      int spectral, int n_iter, double eps, double* log_m,
+                                      const float* hsum, int spectral, int n_iter, double eps, double* log_m,
                                       double* workspace, hipStream_t stream);
 
 // Arguments of the attention kernels (dense and PISA share them).

@@ -6,12 +6,13 @@
 // accuracy.  Two passes over K and V, no per-block matrices in memory:
 //   (1) hsum64_kernel   one workgroup per chunk of blocks accumulates sum_j H_j on the fp64
 //                       matrix cores; the partial sums are added in chunk order and divided
-//                       by N (hbar64_kernel);
+//                       by N (hbar64_kernel).  A caller that accepts Hbar at fp32 accuracy hands
+//                       in the hsum of the statistics pass instead and saves this pass;
 //   (2) frob_kernel     one workgroup per block rebuilds H_j the same way, subtracts Hbar and
 //                       takes the Frobenius norm; or
 //       hetero_kernel   (spectral norm) rebuilds H_j on the vector ALUs, a thread owning an
-//                       R x R patch (R = d/16), and runs a power iteration on D^T D (at most
-//                       the given number of steps, fewer once the estimate stands still).
+//                       R x R patch (R = d/16), and finds the largest eigenvalue of D^T D by a
+//                       locally optimal three-term iteration run to a relative residual.
 #include <hip/hip_bf16.h>
 
 #include "common.h"
@@ -23,15 +24,17 @@ template <typename T> __device__ inline double to_f64(T x);
 template <> __device__ inline double to_f64<float>(float x) { return (double)x; }
 template <> __device__ inline double to_f64<__hip_bfloat16>(__hip_bfloat16 x) { return (double)__bfloat162float(x); }
 
-// h += sum over the rows of block j of (k_n - kbar_j)^T v_n.  kc / vs: LDS staging.
+// h += sum over the rows of block j of (k_n - kbar_j)^T v_n.  kc / vs: LDS staging of kSubV
+// tokens at a time (two workgroups per CU fit their LDS).
+constexpr int kSubV = 32;
 template <typename T, int D>
 __device__ inline void add_block_H(double (&h)[D / 16][D / 16], const T* kh, const T* vh,
                                    const double* kmean /* kbar64 row of block j */, int row0, int rows,
                                    double (*kc)[D], float (*vs)[D]) {
   constexpr int R = D / 16;
   const int tid = threadIdx.x, ta = tid / 16, tb = tid % 16;
-  for (int sub = 0; sub < rows; sub += kTile) {
-    const int nv = min(kTile, rows - sub);
+  for (int sub = 0; sub < rows; sub += kSubV) {
+    const int nv = min(kSubV, rows - sub);
     __syncthreads();
     for (int e = tid; e < nv * D; e += 256) {
       const int n = e / D, c = e % D;
@@ -215,6 +218,13 @@ __global__ __launch_bounds__(256, 2) void frob_kernel(const T* __restrict__ k, c
   if (tid == 0) log_m[bh * N + j] = log(sqrt((red[0] + red[1]) + (red[2] + red[3])) + eps);
 }
 
+// hbar64[bh][e] = hsum[bh][e] / N from the fp32 sum the statistics pass has already produced.
+__global__ __launch_bounds__(256) void hbar_from_hsum_kernel(const float* __restrict__ hsum,
+                                                             double* __restrict__ hbar64, size_t total, int N) {
+  const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (e < total) hbar64[e] = (double)hsum[e] / (double)N;
+}
+
 // hbar64[bh][e] = (sum over chunks, in chunk order, of partial[bh][chunk][e]) / N
 __global__ __launch_bounds__(256) void hbar64_kernel(const double* __restrict__ partial,
                                                      double* __restrict__ hbar64, int n_chunks, int dd, int N) {
@@ -227,31 +237,18 @@ __global__ __launch_bounds__(256) void hbar64_kernel(const double* __restrict__ 
   hbar64[bh * dd + e] = acc / (double)N;
 }
 
-// Sum of one double per thread over the first D threads of the workgroup (D = 64 or 128).
-template <int D>
-__device__ inline double sum_first_threads(double x, double* scratch /* [2] */) {
-  const int tid = threadIdx.x;
-  if (tid >= D) x = 0.0;
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off);
-  __syncthreads();
-  if (tid == 0) scratch[0] = x;
-  if (tid == 64) scratch[1] = x;
-  __syncthreads();
-  return D > 64 ? scratch[0] + scratch[1] : scratch[0];
-}
-
 template <typename T, int D>
-__global__ __launch_bounds__(256) void hetero_kernel(const T* __restrict__ k, const T* __restrict__ v,
+__global__ __launch_bounds__(256, 2) void hetero_kernel(const T* __restrict__ k, const T* __restrict__ v,
                                                      const double* __restrict__ kbar64,
                                                      const double* __restrict__ hbar64,
                                                      double* __restrict__ log_m, int L, int B, int N,
                                                      int spectral, int n_iter, double eps) {
   constexpr int R = D / 16;
-  __shared__ double kc[kTile][D];          // staging; reused as the partial-product board
-  __shared__ float vs[kTile][D];
+  __shared__ double kc[kSubV][D];          // staging; reused as the partial-product board
+  __shared__ float vs[kSubV][D];
+  static_assert(sizeof(double) * kSubV * D >= sizeof(double) * D * 16, "the board must fit the staging area");
   __shared__ double xs[D], ys[D];
-  __shared__ double red[2];
+  __shared__ double dots[2][8];
   const int tid = threadIdx.x, ta = tid / 16, tb = tid % 16;
   const int j = blockIdx.x;
   const size_t bh = blockIdx.y;
@@ -283,19 +280,20 @@ __global__ __launch_bounds__(256) void hetero_kernel(const T* __restrict__ k, co
     __syncthreads();
     m_norm = sqrt((xs[0] + xs[1]) + (xs[2] + xs[3]));
   } else {
-    // Power iteration on D^T D: x <- D^T (D x) / ||.||; then M = ||D x||.
+    // Largest eigenvalue theta of A = D^T D by a locally optimal three-term iteration: each step
+    // takes the best vector (Rayleigh-Ritz) in the span of the iterate x, its residual
+    // r = A x - theta x and the previous step direction p -- the convergence of a Krylov method,
+    // which the closely spaced leading singular values of these matrices need (a plain power
+    // iteration is still 1-2 % short after 48 steps), with three vectors of state.  It stops
+    // once ||r|| <= kRelResidual * theta: some eigenvalue of A then lies within ||r|| of theta,
+    // so M = sqrt(theta) is within kRelResidual / 2 relative of a singular value, and in
+    // practice (the error of a Ritz value is quadratic in the residual) exact to rounding.
+    // Thread t < D holds component t of every vector; all 256 threads share the two products.
     double (*board)[16] = reinterpret_cast<double (*)[16]>(&kc[0][0]);   // [D][16] partial products
-    __syncthreads();
-    if (tid < D) xs[tid] = 1.0 + 0.5 * sin(1.0 + 0.37 * (double)tid);    // fixed, generic start
-    __syncthreads();
-    {
-      const double n2 = sum_first_threads<D>(tid < D ? xs[tid] * xs[tid] : 0.0, red);
-      if (tid < D) xs[tid] /= sqrt(n2);
-    }
-    double ev_prev = 0.0;
-    for (int it = 0; it <= n_iter; ++it) {
+    auto apply_A = [&](double vin) -> double {               // component tid of D^T (D v)
       __syncthreads();
-      // y = D x
+      if (tid < D) xs[tid] = vin;
+      __syncthreads();
 #pragma unroll
       for (int a = 0; a < R; ++a) {
         double pa = 0.0;
@@ -304,18 +302,13 @@ __global__ __launch_bounds__(256) void hetero_kernel(const T* __restrict__ k, co
         board[ta * R + a][tb] = pa;
       }
       __syncthreads();
-      double yv = 0.0;
       if (tid < D) {
+        double yv = 0.0;
 #pragma unroll
         for (int t = 0; t < 16; ++t) yv += board[tid][t];
         ys[tid] = yv;
       }
-      if (it == n_iter) {                      // final: M = ||D x||
-        m_norm = sqrt(sum_first_threads<D>(yv * yv, red));
-        break;
-      }
       __syncthreads();
-      // z = D^T y
 #pragma unroll
       for (int b = 0; b < R; ++b) {
         double pb = 0.0;
@@ -329,14 +322,128 @@ __global__ __launch_bounds__(256) void hetero_kernel(const T* __restrict__ k, co
 #pragma unroll
         for (int t = 0; t < 16; ++t) zv += board[tid][t];
       }
-      const double n2 = sum_first_threads<D>(zv * zv, red);
-      if (tid < D) xs[tid] = n2 > 0.0 ? zv / sqrt(n2) : xs[tid];
-      // ||D^T D x|| with ||x|| = 1 rises towards the largest eigenvalue: once it has stopped
-      // moving (relative step below 1e-4, uniform over the workgroup) the next pass is the last.
-      const double ev = sqrt(n2);
-      if (it >= 3 && it < n_iter - 1 && fabs(ev - ev_prev) <= 1e-4 * ev) it = n_iter - 1;
-      ev_prev = ev;
+      return zv;
+    };
+    // sums of NV per-thread products over the first D threads, the same value in every thread
+    auto reduce = [&](auto& vals) {
+      constexpr int NV = sizeof(vals) / sizeof(double);
+#pragma unroll
+      for (int i = 0; i < NV; ++i) {
+        double x = tid < D ? vals[i] : 0.0;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off);
+        vals[i] = x;
+      }
+      __syncthreads();
+      if ((tid & 63) == 0 && tid < 128) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) dots[tid >> 6][i] = vals[i];
+      }
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < NV; ++i) vals[i] = D > 64 ? dots[0][i] + dots[1][i] : dots[0][i];
+    };
+
+    double x = tid < D ? 1.0 + 0.5 * sin(1.0 + 0.37 * (double)tid) : 0.0;    // fixed, generic start
+    {
+      double n2[1] = {x * x};
+      reduce(n2);
+      x /= sqrt(n2[0]);
     }
+    double ax = apply_A(x);
+    double pv = 0.0, apv = 0.0;                 // previous direction and its image (none yet)
+    bool have_p = false;
+    double theta;
+    {
+      double t1[1] = {x * ax};
+      reduce(t1);
+      theta = t1[0];
+    }
+    for (int it = 0; it < n_iter; ++it) {
+      const double r = ax - theta * x;
+      double d2[4] = {r * r, pv * r, pv * x, pv * pv};
+      reduce(d2);
+      const double rn = sqrt(d2[0]);
+      if (!(rn > kRelResidual * theta)) break;             // converged (also ends on theta = 0 or NaN)
+      const double q2 = r / rn;
+      const double aq2 = apply_A(q2);
+      // p made orthogonal to x and q2 (x is a unit vector and r is orthogonal to it)
+      const double c1 = d2[2], c2 = d2[1] / rn;
+      double q3 = pv - c1 * x - c2 * q2;
+      double aq3 = apv - c1 * ax - c2 * aq2;
+      double g[6] = {x * aq2, x * aq3, q2 * aq2, q2 * aq3, q3 * aq3, q3 * q3};
+      reduce(g);
+      const bool use_p = have_p && g[5] > 1e-24 * d2[3] && g[5] > 0.0;
+      double g01 = g[0], g02 = 0.0, g11 = g[2], g12 = 0.0, g22 = 0.0;
+      if (use_p) {
+        const double inv = 1.0 / sqrt(g[5]);
+        q3 *= inv;
+        aq3 *= inv;
+        g02 = g[1] * inv;
+        g12 = g[3] * inv;
+        g22 = g[4] * inv * inv;
+      }
+      // Largest eigenpair of the symmetric 3 x 3 (or 2 x 2) matrix G = Q^T A Q, Q = [x q2 q3]:
+      // Newton on the characteristic polynomial from an upper bound of the spectrum falls
+      // monotonically onto the largest root; the eigenvector is the largest cross product of
+      // two rows of G - lambda I.
+      const double g00 = theta;
+      double lam = g00 + g11 + g22;                         // trace >= largest eigenvalue (G is positive semi-definite)
+      double e0, e1, e2;
+      if (use_p) {
+        const double tr = g00 + g11 + g22;
+        const double m2 = g00 * g11 + g00 * g22 + g11 * g22 - g01 * g01 - g02 * g02 - g12 * g12;
+        const double det = g00 * (g11 * g22 - g12 * g12) - g01 * (g01 * g22 - g12 * g02) +
+                           g02 * (g01 * g12 - g11 * g02);
+        for (int nt = 0; nt < 60; ++nt) {
+          const double f = ((lam - tr) * lam + m2) * lam - det;
+          const double fp = (3.0 * lam - 2.0 * tr) * lam + m2;
+          if (!(fp > 0.0)) break;
+          const double step = f / fp;
+          lam -= step;
+          if (!(fabs(step) > 1e-16 * fabs(lam))) break;
+        }
+        const double a00 = g00 - lam, a11 = g11 - lam, a22 = g22 - lam;
+        // cross products of row pairs (0,1), (0,2), (1,2)
+        const double u0 = g01 * g12 - g02 * a11, u1 = g02 * g01 - a00 * g12, u2 = a00 * a11 - g01 * g01;
+        const double v0 = g01 * a22 - g02 * g12, v1 = g02 * g02 - a00 * a22, v2 = a00 * g12 - g01 * g02;
+        const double w0 = a11 * a22 - g12 * g12, w1 = g12 * g02 - g01 * a22, w2 = g01 * g12 - a11 * g02;
+        const double nu = u0 * u0 + u1 * u1 + u2 * u2, nv = v0 * v0 + v1 * v1 + v2 * v2,
+                     nw = w0 * w0 + w1 * w1 + w2 * w2;
+        if (nu >= nv && nu >= nw) { e0 = u0; e1 = u1; e2 = u2; }
+        else if (nv >= nw) { e0 = v0; e1 = v1; e2 = v2; }
+        else { e0 = w0; e1 = w1; e2 = w2; }
+        const double en = sqrt(e0 * e0 + e1 * e1 + e2 * e2);
+        if (!(en > 0.0)) { e0 = 1.0; e1 = e2 = 0.0; }       // G is a multiple of the identity
+        else { e0 /= en; e1 /= en; e2 /= en; }
+      } else {
+        const double half = 0.5 * (g00 - g11);
+        lam = 0.5 * (g00 + g11) + sqrt(half * half + g01 * g01);
+        e0 = g01;
+        e1 = lam - g00;
+        if (fabs(lam - g11) > fabs(e1)) { e0 = lam - g11; e1 = g01; }
+        e2 = 0.0;
+        const double en = sqrt(e0 * e0 + e1 * e1);
+        if (!(en > 0.0)) { e0 = 1.0; e1 = 0.0; }
+        else { e0 /= en; e1 /= en; }
+      }
+      if (e0 < 0.0) { e0 = -e0; e1 = -e1; e2 = -e2; }
+      // new iterate; the part of it outside the old x is the next direction
+      pv = e1 * q2 + e2 * q3;
+      apv = e1 * aq2 + e2 * aq3;
+      x = e0 * x + pv;
+      ax = e0 * ax + apv;
+      have_p = true;
+      // theta = x.Ax / x.x of the vector actually held (x drifts off unit length by rounding only);
+      // the residual of the next step is orthogonal to x only with this theta
+      double t2[2] = {x * ax, x * x};
+      reduce(t2);
+      const double inv = 1.0 / sqrt(t2[1]);
+      x *= inv;
+      ax *= inv;
+      theta = t2[0] / t2[1];
+    }
+    m_norm = theta > 0.0 ? sqrt(theta) : 0.0;
   }
   if (tid == 0) log_m[bh * N + j] = log(m_norm + eps);
 }
@@ -349,7 +456,7 @@ size_t hetero_workspace_bytes(const Dims& dm) {
 }
 
 hipError_t launch_block_heterogeneity(const Dims& dm, const void* k, const void* v, const double* kbar64,
-                                      int spectral, int n_iter, double eps, double* log_m,
+                                      const float* hsum, int spectral, int n_iter, double eps, double* log_m,
                                       double* workspace, hipStream_t stream) {
   const StatsPlan plan = stats_plan(dm);
   const int dd = dm.d * dm.d;
@@ -358,9 +465,15 @@ hipError_t launch_block_heterogeneity(const Dims& dm, const void* k, const void*
   const dim3 g1(plan.n_chunks, dm.bh()), g2((dd + 255) / 256, dm.bh()), g3(dm.N, dm.bh());
 #define PISA_HET(T, DD)                                                                                \
   do {                                                                                                  \
-    hipLaunchKernelGGL((hsum64_kernel<T, DD>), g1, dim3(256), 0, stream, (const T*)k, (const T*)v,      \
-                       kbar64, partial, dm.L, dm.B, dm.N, plan.chunk_blocks, plan.n_chunks);            \
-    hipLaunchKernelGGL(hbar64_kernel, g2, dim3(256), 0, stream, partial, hbar, plan.n_chunks, dd, dm.N); \
+    if (hsum) {                                                                                         \
+      const size_t total = (size_t)dm.bh() * dd;                                                        \
+      hipLaunchKernelGGL(hbar_from_hsum_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, \
+                         hsum, hbar, total, dm.N);                                                      \
+    } else {                                                                                            \
+      hipLaunchKernelGGL((hsum64_kernel<T, DD>), g1, dim3(256), 0, stream, (const T*)k, (const T*)v,    \
+                         kbar64, partial, dm.L, dm.B, dm.N, plan.chunk_blocks, plan.n_chunks);          \
+      hipLaunchKernelGGL(hbar64_kernel, g2, dim3(256), 0, stream, partial, hbar, plan.n_chunks, dd, dm.N); \
+    }                                                                                                   \
     if (spectral)                                                                                       \
       hipLaunchKernelGGL((hetero_kernel<T, DD>), g3, dim3(256), 0, stream, (const T*)k, (const T*)v,    \
                          kbar64, hbar, log_m, dm.L, dm.B, dm.N, spectral, n_iter, eps);                 \

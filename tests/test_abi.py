@@ -74,7 +74,7 @@ def test_bad_shapes_are_rejected(kw, code):
     assert pisa.last_error() != ""
     assert lib.pisa_attention(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 1, FAKE, None, FAKE, 1 << 40, None) == code
     assert lib.pisa_select(ctypes.byref(s), FAKE, FAKE, None, 1, FAKE, None, FAKE, 1 << 40, None) == code
-    assert lib.pisa_block_heterogeneity(ctypes.byref(s), FAKE, FAKE, FAKE, 0, 1e-6, FAKE, FAKE, 1 << 40, None) == code
+    assert lib.pisa_block_heterogeneity(ctypes.byref(s), FAKE, FAKE, FAKE, None, 0, 1e-6, FAKE, FAKE, 1 << 40, None) == code
     assert lib.pisa_block_stats(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE,
                                 FAKE, 1 << 40, None) == code
 
@@ -101,11 +101,11 @@ def test_null_and_range_arguments():
     assert "workspace" in pisa.last_error()
     assert lib.pisa_block_stats(ctypes.byref(s), FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE,
                                 FAKE, 1 << 40, None) == pisa.PISA_INVALID_ARG
-    assert lib.pisa_block_heterogeneity(ctypes.byref(s), FAKE, FAKE, FAKE, 5, 1e-6, FAKE, FAKE, 1 << 40, None) \
+    assert lib.pisa_block_heterogeneity(ctypes.byref(s), FAKE, FAKE, FAKE, None, 5, 1e-6, FAKE, FAKE, 1 << 40, None) \
         == pisa.PISA_INVALID_ARG
-    assert lib.pisa_block_heterogeneity(ctypes.byref(s), FAKE, FAKE, FAKE, 0, -1.0, FAKE, FAKE, 1 << 40, None) \
+    assert lib.pisa_block_heterogeneity(ctypes.byref(s), FAKE, FAKE, FAKE, None, 0, -1.0, FAKE, FAKE, 1 << 40, None) \
         == pisa.PISA_INVALID_ARG
-    assert lib.pisa_block_heterogeneity(ctypes.byref(s), FAKE, FAKE, FAKE, 1, 1e-6, FAKE, FAKE, 64, None) \
+    assert lib.pisa_block_heterogeneity(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, 1, 1e-6, FAKE, FAKE, 64, None) \
         == pisa.PISA_WORKSPACE_TOO_SMALL
     big = shape(seq_len=64 * 5000)
     assert lib.pisa_select(ctypes.byref(big), FAKE, FAKE, None, 4, FAKE, None, FAKE, 1 << 60, None) == pisa.PISA_UNSUPPORTED
@@ -125,7 +125,7 @@ def test_misaligned_pointers_are_rejected():
     assert lib.pisa_select(ctypes.byref(s), FAKE, FAKE, None, 4, FAKE, None, odd, 1 << 40, None) == pisa.PISA_INVALID_ARG
     assert lib.pisa_block_stats(ctypes.byref(s), odd, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 40,
                                 None) == pisa.PISA_INVALID_ARG
-    assert lib.pisa_block_heterogeneity(ctypes.byref(s), FAKE, FAKE, FAKE, 1, 1e-6, odd, FAKE, 1 << 40, None) \
+    assert lib.pisa_block_heterogeneity(ctypes.byref(s), FAKE, FAKE, FAKE, None, 1, 1e-6, odd, FAKE, 1 << 40, None) \
         == pisa.PISA_INVALID_ARG
 
 

@@ -249,10 +249,10 @@ def test_covariance_aware_selection(lib, dtype, d, B, L):
     shape = lib.make_shape(qd, B)
     st_gpu = lib.block_stats(qd, kd, vd, B)
     N, k_top = wl_blocks(w), wl_topk(w)
-    # Frobenius is exact (fp64); the spectral norm comes from 48 power-iteration steps, which
-    # approach the largest singular value from below and, for these nearly-flat spectra
-    # (rank <= block size, closely spaced singular values), stop a few percent short.
-    for norm, kind, tol in ((lib.PISA_NORM_FROBENIUS, "frobenius", 1e-9), (lib.PISA_NORM_SPECTRAL, "spectral", 5e-2)):
+    # Both norms are fp64: Frobenius directly, the spectral norm as the square root of the largest
+    # eigenvalue of D^T D from an iteration run to a relative residual of 1e-7, whose Ritz value
+    # (error quadratic in the residual) equals the oracle's SVD value to rounding.
+    for norm, kind, tol in ((lib.PISA_NORM_FROBENIUS, "frobenius", 1e-9), (lib.PISA_NORM_SPECTRAL, "spectral", 1e-9)):
         log_m = lib.block_heterogeneity(shape, kd, vd, st_gpu["kbar64"], norm, 1e-6)
         idx, gap = lib.select(shape, st_gpu["qbar64"], st_gpu["kbar64"], k_top, col_bias=log_m)
         torch.cuda.synchronize()
@@ -263,15 +263,31 @@ def test_covariance_aware_selection(lib, dtype, d, B, L):
             got = log_m[0, h].cpu().numpy()
             assert np.abs(np.exp(got) - (M + 1e-6)).max() <= tol * M.max(), (kind, h)
             if kind == "spectral":
-                assert np.all(np.exp(got) <= (M + 1e-6) * (1 + 1e-9)), "power iteration is a lower bound"
+                assert np.all(np.exp(got) <= (M + 1e-6) * (1 + 1e-9)), "a Ritz value never exceeds the largest eigenvalue"
             # the select stage is judged on the bias it was given ...
             ref, gref = po.select(st["qbar"], st["kbar"], scale, k_top, col_bias=got)
             check_select(idx[0, h].cpu().numpy(), gap[0, h].cpu().numpy().astype(np.float64), ref, gref, N,
                          where=f" cov {kind} head {h}")
-            # ... and against the oracle's own bias it may differ only where the gap is within the norm's accuracy
+            # ... and against the oracle's own bias by the same rule as everywhere: rows may differ only
+            # where the oracle's k-th gap is below 1e-6
             ref2, gref2 = po.select(st["qbar"], st["kbar"], scale, k_top, col_bias=np.log(M + 1e-6))
-            diff = np.any(idx[0, h].cpu().numpy() != ref2, axis=1)
-            assert not np.any(diff & (gref2 > 2 * tol)), (kind, h)
+            check_select(idx[0, h].cpu().numpy(), gap[0, h].cpu().numpy().astype(np.float64), ref2, gref2, N,
+                         where=f" cov {kind} head {h} (oracle bias)")
+    # Hbar from the fp32 hsum of the statistics pass (saves the fp64 pass that rebuilds it): hsum is good to
+    # about 1e-6 of its largest entry and ||Hbar|| is a fraction of ||H_j - Hbar||, so M_j moves by well under
+    # 1e-6 relative and the selection obeys the same 1e-6 gap rule against the oracle's own bias.
+    for norm, kind in ((lib.PISA_NORM_FROBENIUS, "frobenius"), (lib.PISA_NORM_SPECTRAL, "spectral")):
+        log_m = lib.block_heterogeneity(shape, kd, vd, st_gpu["kbar64"], norm, 1e-6, hsum=st_gpu["hsum"])
+        idx, gap = lib.select(shape, st_gpu["qbar64"], st_gpu["kbar64"], k_top, col_bias=log_m)
+        torch.cuda.synchronize()
+        for h in range(w.heads):
+            Q, K, V = head_np(q, 0, h), head_np(k, 0, h), head_np(v, 0, h)
+            st = po.block_stats(Q, K, V, B, per_block_H=True)
+            M = po.block_heterogeneity(st["Hj"], st["hsum"], kind)
+            got = log_m[0, h].cpu().numpy()
+            assert np.abs(np.exp(got) - (M + 1e-6)).max() <= 1e-6 * M.max(), (kind, h)
+            ref2, gref2 = po.select(st["qbar"], st["kbar"], scale, k_top, col_bias=np.log(M + 1e-6))
+            check_select(idx[0, h].cpu().numpy(), None, ref2, gref2, N, where=f" cov {kind} head {h} (Hbar from hsum)")
     # end to end with the covariance-aware score
     res = lib.pisa_forward(qd, kd, vd, B, w.sparsity, covariance_aware=True, norm=lib.PISA_NORM_FROBENIUS)
     torch.cuda.synchronize()
