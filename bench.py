@@ -277,17 +277,19 @@ def main():
     achieved = fl_attn / (attn_ms * 1e-3) / 1e12
     # HBM-side traffic of the attention kernel per launch comes from separate rocprofv3 --pmc
     # runs (counters cannot be read from inside this process); the committed summary applies
-    # to the default workload only.
+    # to the default workload only and names the commit whose build it profiled.
     traffic = traffic_detail = None
     tj = args.traffic_json
     if tj is None and args.workload == "wan" and args.sparsity is None and args.block is None:
-        tj = os.path.join(ROOT, "profiles", "wan_r085_traffic.txt")
+        tj = os.path.join(ROOT, "profiles", "wan_r085_traffic.json")
     if tj and os.path.exists(tj):
         with open(tj) as f:
             t = json.load(f)
         traffic = t["fetch_bytes"] + t["write_bytes"]        # bytes per launch past the L2
         traffic_detail = {"fetch_bytes": t["fetch_bytes"], "write_bytes": t["write_bytes"],
-                          "algorithmic_bytes": t.get("algorithmic_bytes"), "source": t.get("source")}
+                          "algorithmic_bytes": t.get("algorithmic_bytes"), "source": t.get("source"),
+                          "measured_in_this_run": False,       # counters come from a separate rocprofv3 --pmc run
+                          "profiled_commit": t.get("commit")}
     in_bytes = 3 * q.numel() * q.element_size()
     result = {
         "metric": "PISA attn ms/call & MFMA util at Wan2.1 shape, r=0.85; speedup vs dense",

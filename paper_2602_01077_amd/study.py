@@ -7,6 +7,9 @@
          sum|O - O_dense| / sum|O_dense|, for the keep-or-drop, zeroth-order and hybrid
          variants over a range of densities (the quantity of the paper's ablation figure
          "Relative error with respect to dense attention", here on synthetic inputs).
+`error --lengths L1 L2 ...`  the same three errors at ONE density over sequence lengths (the
+         length axis of that figure): the Wan-style generator on a t x 45 x 80 latent grid cut
+         to the length asked for.
 `speed`  ms per call of dense_attention and of the whole PISA path over sequence lengths
          and densities at the paper's kernel-study shape B2-H16-D128 ("Kernel Efficiency
          Evaluation").
@@ -35,7 +38,39 @@ def _time_ms(fn, iters):
     return e0.elapsed_time(e1) / iters
 
 
+def _error_row(w, q, k, v, r, row):
+    dense, _ = pisa.dense_attention(q, k, v, w.block)
+    den = dense.float().abs().sum().item()
+    n = pisa.num_blocks(w.seq_len, w.block)
+    for name, kw in (("keep_or_drop", dict(approximate=False)),
+                     ("zeroth_order", dict(first_order=False)),
+                     ("hybrid", dict())):
+        if name == "keep_or_drop" and pisa.topk_count(n, r) == 0:
+            row[name] = None
+            continue
+        out = pisa.pisa_forward(q, k, v, w.block, r, **kw)["out"]
+        row[name] = (out.float() - dense.float()).abs().sum().item() / den
+    print(json.dumps(row), flush=True)
+
+
+def error_vs_length(args):
+    """Fixed density, growing length (the paper's second error plot: 20 % density)."""
+    base = WORKLOADS["wan"]
+    r = args.sparsity[0]
+    heads = list(range(0, base.heads, max(1, base.heads // args.heads)))[: args.heads]
+    for L in args.lengths:
+        frames = -(-L // (45 * 80))
+        w = base.with_(name=f"wan-L{L}", seq_len=L, grid=(frames, 45, 80))
+        # the generator lays the field over whole frames; the sequence is its first L tokens
+        full = w.with_(seq_len=frames * 45 * 80)
+        q, k, v = (x[:, :, :L].contiguous() for x in make_qkv(full, device="cuda:0", heads=heads))
+        _error_row(w, q, k, v, r, {"workload": w.name, "heads": len(heads), "seq_len": L, "block": w.block,
+                                   "sparsity": r, "density": round(1 - r, 4)})
+
+
 def error_study(args):
+    if args.lengths:
+        return error_vs_length(args)
     w = WORKLOADS[args.workload]
     heads = list(range(0, w.heads, max(1, w.heads // args.heads)))[: args.heads]
     q, k, v = make_qkv(w, device="cuda:0", heads=heads)
@@ -99,6 +134,8 @@ def main():
     e.add_argument("--workload", default="wan", choices=list(WORKLOADS))
     e.add_argument("--heads", type=int, default=8)
     e.add_argument("--sparsity", type=float, nargs="+", default=[0.5, 0.75, 0.8, 0.85, 0.875, 0.9, 0.95])
+    e.add_argument("--lengths", type=int, nargs="+", default=None,
+                   help="sweep the sequence length at the first --sparsity instead of sweeping the density")
     s = sub.add_parser("speed")
     s.add_argument("--lengths", type=int, nargs="+", default=[4096, 8192, 16384, 32768, 65536])
     s.add_argument("--sparsity", type=float, nargs="+", default=[0.3, 0.5, 0.7, 0.875])
