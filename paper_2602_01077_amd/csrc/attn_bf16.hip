@@ -789,68 +789,80 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void attn_bf16_kernel(PB p) {
   // O^T += V(t)^T P(t)^T, and last S^T(t+1), which takes over the score registers the softmax
   // has just consumed.  Where trips can be split (block 64, PISA) every step comes in two halves
   // of 32 keys, each guarded by its bit of the trip's work mask (both set in a full trip).
-  constexpr bool SPLITS = !DENSE && TPB == 1;
+  // A block-64 workgroup whose two lists coincide has no split trip at all: it runs the copy of
+  // the loop without the guards (the code the dense kernel runs), so that r = 0 costs what the
+  // dense kernel costs.
   const int my_shift = (int)(lc.wave >> 1) * 2;
-  int lo0 = 0, hi0 = 0, wm0 = 0, lo1 = 0, hi1 = 0, wm1 = 0, lo2 = 0, hi2 = 0, wm2 = 0;
-  bool have0 = next_trip(lo0, hi0, wm0);
-  bool have1 = false, have2 = false;
   f32x16 sc0, sc1;                       // S^T of the current trip: stage rows 0..31 / 32..63
-  auto scores = [&](auto koff_tag, int wm) {
-    constexpr int KOFF = decltype(koff_tag)::value;
-    if (!SPLITS) {
-      qk_tile<D, KOFF>(sc0, sc1, qreg, lc);
-    } else {
-      if ((wm >> my_shift) & 1) qk_rows<D, KOFF, 0>(sc0, qreg, lc);
-      if ((wm >> my_shift) & 2) qk_rows<D, KOFF, 32>(sc1, qreg, lc);
+  auto walk = [&](auto splits_tag) {
+    constexpr bool SPLITS = decltype(splits_tag)::value;
+    int lo0 = 0, hi0 = 0, wm0 = 0, lo1 = 0, hi1 = 0, wm1 = 0, lo2 = 0, hi2 = 0, wm2 = 0;
+    bool have0 = next_trip(lo0, hi0, wm0);
+    bool have1 = false, have2 = false;
+    auto scores = [&](auto koff_tag, int wm) {
+      constexpr int KOFF = decltype(koff_tag)::value;
+      if (!SPLITS) {
+        qk_tile<D, KOFF>(sc0, sc1, qreg, lc);
+      } else {
+        if ((wm >> my_shift) & 1) qk_rows<D, KOFF, 0>(sc0, qreg, lc);
+        if ((wm >> my_shift) & 2) qk_rows<D, KOFF, 32>(sc1, qreg, lc);
+      }
+    };
+    if (have0) {
+      load_stage<D, true>(lc, kg, Trip{lo0, hi0}, lds_addr + KST0);
+      have1 = next_trip(lo1, hi1, wm1);
+      wait_async_loads();
+      __syncthreads();
+      if (have1) load_stage<D, true>(lc, kg, Trip{lo1, hi1}, lds_addr + KST1);
+      load_stage<D, false>(lc, vg, Trip{lo0, hi0}, lds_addr + VST0);
+      scores(std::integral_constant<int, KST0>{}, wm0);
     }
-  };
-  if (have0) {
-    load_stage<D, true>(lc, kg, Trip{lo0, hi0}, lds_addr + KST0);
-    have1 = next_trip(lo1, hi1, wm1);
-    wait_async_loads();
-    __syncthreads();
-    if (have1) load_stage<D, true>(lc, kg, Trip{lo1, hi1}, lds_addr + KST1);
-    load_stage<D, false>(lc, vg, Trip{lo0, hi0}, lds_addr + VST0);
-    scores(std::integral_constant<int, KST0>{}, wm0);
-  }
-  auto trip = [&](auto parity_tag) {
-    constexpr int P = decltype(parity_tag)::value;       // parity of the current trip
-    constexpr int K_NEXT = P ? KST0 : KST1, K_FREE = P ? KST1 : KST0;
-    constexpr int V_CUR = P ? VST1 : VST0, V_FREE = P ? VST0 : VST1;
-    have2 = have1 && next_trip(lo2, hi2, wm2);
-    wait_async_loads();
-    __syncthreads();
-    // Past the end of the walk the loads repeat trip 0's sources into the free stages (harmless).
-    load_stage<D, true>(lc, kg, Trip{have2 ? lo2 : lo0, have2 ? hi2 : hi0}, lds_addr + K_FREE);
-    load_stage<D, false>(lc, vg, Trip{have1 ? lo1 : lo0, have1 ? hi1 : hi0}, lds_addr + V_FREE);
-    const bool do_lo = !SPLITS || ((wm0 >> my_shift) & 1), do_hi = !SPLITS || ((wm0 >> my_shift) & 2);
-    if (do_lo || do_hi) {
-      bf16x8 pb[4];
-      float nm = -st.m, pa = 0.f, pc = 0.f;
-      if (do_lo) exp_rows(sc0, c, nm, pb[0], pb[1], pa, pc);
-      if (do_hi) exp_rows(sc1, c, nm, pb[2], pb[3], pa, pc);
-      if (__any(!(pa + pc < kStaleLimit))) {         // first keys of this wave, or a maximum that ran away
-        float t = -INFINITY;
-        if (do_lo) t = max_rows(sc0);
-        if (do_hi) t = fmaxf(t, max_rows(sc1));
-        raise_max<D>(st, t * c);
-        nm = -st.m;
-        pa = pc = 0.f;
+    auto trip = [&](auto parity_tag) {
+      constexpr int P = decltype(parity_tag)::value;       // parity of the current trip
+      constexpr int K_NEXT = P ? KST0 : KST1, K_FREE = P ? KST1 : KST0;
+      constexpr int V_CUR = P ? VST1 : VST0, V_FREE = P ? VST0 : VST1;
+      have2 = have1 && next_trip(lo2, hi2, wm2);
+      wait_async_loads();
+      __syncthreads();
+      // Past the end of the walk the loads repeat trip 0's sources into the free stages (harmless).
+      load_stage<D, true>(lc, kg, Trip{have2 ? lo2 : lo0, have2 ? hi2 : hi0}, lds_addr + K_FREE);
+      load_stage<D, false>(lc, vg, Trip{have1 ? lo1 : lo0, have1 ? hi1 : hi0}, lds_addr + V_FREE);
+      const bool do_lo = !SPLITS || ((wm0 >> my_shift) & 1), do_hi = !SPLITS || ((wm0 >> my_shift) & 2);
+      if (do_lo || do_hi) {
+        bf16x8 pb[4];
+        float nm = -st.m, pa = 0.f, pc = 0.f;
         if (do_lo) exp_rows(sc0, c, nm, pb[0], pb[1], pa, pc);
         if (do_hi) exp_rows(sc1, c, nm, pb[2], pb[3], pa, pc);
+        if (__any(!(pa + pc < kStaleLimit))) {         // first keys of this wave, or a maximum that ran away
+          float t = -INFINITY;
+          if (do_lo) t = max_rows(sc0);
+          if (do_hi) t = fmaxf(t, max_rows(sc1));
+          raise_max<D>(st, t * c);
+          nm = -st.m;
+          pa = pc = 0.f;
+          if (do_lo) exp_rows(sc0, c, nm, pb[0], pb[1], pa, pc);
+          if (do_hi) exp_rows(sc1, c, nm, pb[2], pb[3], pa, pc);
+        }
+        st.l += pa + pc;
+        if (do_lo) pv_rows<D, V_CUR, 0>(st, pb[0], pb[1], lc);
+        if (do_hi) pv_rows<D, V_CUR, 32>(st, pb[2], pb[3], lc);
       }
-      st.l += pa + pc;
-      if (do_lo) pv_rows<D, V_CUR, 0>(st, pb[0], pb[1], lc);
-      if (do_hi) pv_rows<D, V_CUR, 32>(st, pb[2], pb[3], lc);
+      if (have1) scores(std::integral_constant<int, K_NEXT>{}, wm1);
+      lo0 = lo1; hi0 = hi1; wm0 = wm1; have0 = have1;
+      lo1 = lo2; hi1 = hi2; wm1 = wm2; have1 = have2;
+    };
+    while (have0) {
+      trip(std::integral_constant<int, 0>{});
+      if (!have0) break;
+      trip(std::integral_constant<int, 1>{});
     }
-    if (have1) scores(std::integral_constant<int, K_NEXT>{}, wm1);
-    lo0 = lo1; hi0 = hi1; wm0 = wm1; have0 = have1;
-    lo1 = lo2; hi1 = hi2; wm1 = wm2; have1 = have2;
   };
-  while (have0) {
-    trip(std::integral_constant<int, 0>{});
-    if (!have0) break;
-    trip(std::integral_constant<int, 1>{});
+  if (!DENSE && TPB == 1) {
+    const bool any_split = n_entries != __builtin_amdgcn_readfirstlane((int)pre_s[MASK_WORDS]);
+    if (any_split) walk(std::true_type{});
+    else walk(std::false_type{});
+  } else {
+    walk(std::false_type{});
   }
   wait_async_loads();                      // the last trips' repeated loads
 
