@@ -921,8 +921,26 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void attn_bf16_kernel(PB p) {
   st.l_tail += __shfl_xor(st.l_tail, 32);
 
   // ---- Phase 3: R^T = hsum^T (d_out x d_in) * Q^T (d_in x queries), weight l_tail / L * s ----
+  // The packed matrix (hi and lo halves, 4 D^2 bytes: the size of the staging area at head_dim
+  // 128) goes through LDS once per workgroup instead of once per wave from L2: it is stored in
+  // operand order, 16 bytes per lane, so the copy is a straight LDS-DMA and the reads are
+  // conflict-free ds_read_b128.
   if (approx && p.first_order) {
-    const bf16x8* hp = reinterpret_cast<const bf16x8*>(p.hpack + bh * (size_t)(2 * D * D));
+    const unsigned char* hp = reinterpret_cast<const unsigned char*>(p.hpack + bh * (size_t)(2 * D * D));
+    constexpr int HP_BYTES = 4 * D * D, HP_LOADS = HP_BYTES / (4 * 1024);     // 1 KB wave-loads per wave
+    static_assert(HP_BYTES <= 4 * TILEB, "the packed matrix must fit the staging area");
+    __syncthreads();                            // every wave is done with the centroid stages
+#pragma unroll
+    for (int i = 0; i < HP_LOADS; ++i) {
+      const unsigned off = (unsigned)__builtin_amdgcn_readfirstlane((int)((lc.wave * HP_LOADS + i) * 1024));
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                   :
+                   : "s"(lds_addr + off), "v"((unsigned)(lane * 16)), "s"(hp + off)
+                   : "memory", "m0");
+    }
+    wait_async_loads();
+    __syncthreads();
+    LDS_PTR(const unsigned char) hl = lds + lane * 16;
     f32x16 rt[NDT];
 #pragma unroll
     for (int dt = 0; dt < NDT; ++dt) rt[dt] = (f32x16){0};
@@ -930,8 +948,8 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void attn_bf16_kernel(PB p) {
     for (int ks = 0; ks < NKS; ++ks)
 #pragma unroll
       for (int dt = 0; dt < NDT; ++dt) {
-        const bf16x8 ahi = hp[(ks * NDT + dt) * 64 + lane];
-        const bf16x8 alo = hp[D * D / 8 + (ks * NDT + dt) * 64 + lane];
+        const bf16x8 ahi = *reinterpret_cast<LDS_PTR(const bf16x8)>(hl + (ks * NDT + dt) * 1024);
+        const bf16x8 alo = *reinterpret_cast<LDS_PTR(const bf16x8)>(hl + 2 * D * D + (ks * NDT + dt) * 1024);
         rt[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ahi, qreg[ks], rt[dt], 0, 0, 0);
         rt[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(alo, qreg[ks], rt[dt], 0, 0, 0);
       }
