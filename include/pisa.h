@@ -169,12 +169,12 @@ int32_t pisa_attention(const pisa_shape* shape, const void* q, const void* k, co
 /*
  * pisa_attention for callers that cannot allocate or carry a workspace: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
- * kernels and the same result bit for bit; the scratch (bf16 centroid tiles, packed hsum,
- * column bias) lives in a device array inside the library of PISA_STATIC_SCRATCH_BYTES, which
+ * kernels and the same result bit for bit; the scratch (bf16 centroid tiles, packed hsum)
+ * lives in a device array inside the library of PISA_STATIC_SCRATCH_BYTES, which
  * every GPU the library runs on holds until the process ends.  The call allocates and frees
  * nothing and does not synchronise.
- *   - Shapes whose scratch need (batch * heads * (4 * ceil(N / 64) * 64 * d + 4 * d * d) bytes
- *     + 4 * ceil(N / 64) * 64, bf16 path) exceeds the array return PISA_WORKSPACE_TOO_SMALL before
+ *   - Shapes whose scratch need (batch * heads * (4 * ceil(N / 64) * 64 * d + 4 * d * d) bytes,
+ *     bf16 path) exceeds the array return PISA_WORKSPACE_TOO_SMALL before
  *     any device work; the three bf16 shapes of the paper's models fit.
  *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU
  *     (different streams, or threads) race on it.  Calls on one stream are ordered and safe.

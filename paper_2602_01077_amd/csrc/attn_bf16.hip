@@ -74,7 +74,6 @@ struct PB {
   const __bf16* v;
   const __bf16* kcen;     // [bh][npad][D] kbar_j rounded to bf16    (pre-pass)
   const __bf16* vbar;     // [bh][npad][D] vsum_j / B_j
-  const float* bias;      // [npad] log2 B_j, -inf past N
   const __bf16* hpack;    // [bh][2][D/16 ks][D/32 dt][64 lanes][8] hsum^T hi / lo in A-operand order
   const int32_t* idx;
   __bf16* out;
@@ -104,7 +103,7 @@ template <int D>
 __global__ __launch_bounds__(256) void attn_prep_kernel(
     const float* __restrict__ kbar, const float* __restrict__ vsum, const float* __restrict__ hsum,
     __bf16* __restrict__ kcen, __bf16* __restrict__ vbar,
-    float* __restrict__ bias, __bf16* __restrict__ hpack, int L, int B, int N, int npad) {
+    __bf16* __restrict__ hpack, int L, int B, int N, int npad) {
   const int tid = threadIdx.x;
   const size_t bh = blockIdx.y;
   const int g = blockIdx.x;
@@ -132,10 +131,6 @@ __global__ __launch_bounds__(256) void attn_prep_kernel(
       const size_t o = (size_t)j * ROWB + c4 * 2;
       *reinterpret_cast<u32x2*>(ok + o) = kc;
       *reinterpret_cast<u32x2*>(ov + o) = vb;
-    }
-    if (bh == 0 && tid < kTile) {
-      const int j = g * kTile + tid;
-      bias[j] = j < N ? __builtin_amdgcn_logf((float)(j == N - 1 ? last_rows : B)) : -INFINITY;
     }
   } else if (hsum) {
     // hpack[part][ks][dt][lane][e] = part(hsum[d_in = 16 ks + 8 h + e][d_out = 32 dt + lam]);
@@ -566,6 +561,20 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void attn_bf16_kernel(PB p) {
     lc.vbase = lds + kq * ROWB + 8 * (j16 & 3) + ((lhalf ^ vswz<D>(kq)) << 5);
   }
 
+  // The first 256 entries of each block's index row are requested before anything else: they
+  // head the chain index row -> trip list -> first tile load, and the Q operand loads queue
+  // up behind them.
+  constexpr int nqb = (!DENSE && tpb == 1) ? 2 : 1;
+  int j_first[nqb];
+  if (!DENSE) {
+#pragma unroll
+    for (int b = 0; b < nqb; ++b) {
+      const int i = tpb == 1 ? 2 * sg + b : sg;
+      j_first[b] = -1;
+      if (i < N && tid < p.k_top) j_first[b] = p.idx[(bh * N + i) * (size_t)p.k_top + tid];
+    }
+  }
+
   // ---- Q^T operand: this lane's query row, D/16 channel slices of 16 ----
   const int q_row = sg * QROWS + 32 * wave + lam;
   bf16x8 qreg[NKS];
@@ -591,13 +600,14 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void attn_bf16_kernel(PB p) {
   if (!DENSE) {
     for (int w = tid; w < 2 * MASK_WORDS; w += 256) (&chosen[0][0])[w] = 0u;
     __syncthreads();
-    const int nqb = tpb == 1 ? 2 : 1;
+#pragma unroll
     for (int b = 0; b < nqb; ++b) {
       const int i = tpb == 1 ? 2 * sg + b : sg;
       if (i < N) {
         const int32_t* row = p.idx + (bh * N + i) * (size_t)p.k_top;
+        int j = j_first[b];
         for (int t = tid; t < p.k_top; t += 256) {
-          const int j = row[t];
+          if (t != tid) j = row[t];
           if ((unsigned)j < (unsigned)N)          // entries outside [0, N) are ignored
             atomicOr(&chosen[b][j >> 5], 1u << (j & 31));
         }
@@ -888,7 +898,9 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void attn_bf16_kernel(PB p) {
   if (approx) {
     const unsigned char* kcg = reinterpret_cast<const unsigned char*>(p.kcen + bh * (size_t)p.npad * D);
     const unsigned char* vbg = reinterpret_cast<const unsigned char*>(p.vbar + bh * (size_t)p.npad * D);
-    // Double buffered: tile g + 1 (and its bias vector) is fetched while tile g is absorbed.
+    // Double buffered: tile g + 1 (and its column bias) is fetched while tile g is absorbed.
+    const float log2_full = __builtin_amdgcn_logf((float)p.B);
+    const float log2_last = __builtin_amdgcn_logf((float)(L - (N - 1) * p.B));
     auto fetch = [&](int g0, auto parity_tag) {
       constexpr int P = decltype(parity_tag)::value;
       load_tile_async<D, true>(lc, kcg + (size_t)g0 * ROWB, kTile, lds_addr + (P ? KST1 : KST0));
@@ -897,7 +909,10 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void attn_bf16_kernel(PB p) {
         const int b = tid >> 6, j = g0 + (tid & 63);
         const bool masked =
             (tpb == 2 && b == 1) ? true : ((chosen[b][(j >> 5) & (MASK_WORDS - 1)] >> (j & 31)) & 1u);
-        bias_s[P][b][tid & 63] = masked ? -INFINITY : p.bias[j];
+        // log2 B_j for a centroid that stands for its block; computed here (two values per
+        // call), so that no ordinary load, and with it no wait on the tile loads just issued,
+        // sits in this step
+        bias_s[P][b][tid & 63] = (masked || j >= N) ? -INFINITY : (j == N - 1 ? log2_last : log2_full);
       }
     };
     auto absorb = [&](int g0, auto parity_tag) {
@@ -981,7 +996,7 @@ size_t attention_workspace_bytes(const Dims& dm) {
   if (dm.dtype != PISA_BF16) return 0;
   const size_t npad = (size_t)((dm.N + kTile - 1) / kTile) * kTile;
   const size_t D = dm.d;
-  return (size_t)dm.bh() * (2 * npad * D * 2 + 2 * D * D * 2) + npad * sizeof(float);
+  return (size_t)dm.bh() * (2 * npad * D * 2 + 2 * D * D * 2);
 }
 
 template <int D>
@@ -1008,21 +1023,19 @@ static hipError_t launch_attention_bf16_d(const Dims& dm, const AttnArgs& a, hip
     return hipGetLastError();
   }
   if (a.k_top < dm.N && a.kbar) {
-    // carve the workspace: kcen | vbar | hpack | bias
+    // carve the workspace: kcen | vbar | hpack
     unsigned char* ws = static_cast<unsigned char*>(a.workspace);
     const size_t tile_elems = (size_t)dm.bh() * p.npad * D;
     __bf16* kcen = reinterpret_cast<__bf16*>(ws);
     __bf16* vbar = kcen + tile_elems;
     __bf16* hpack = vbar + tile_elems;
-    float* bias = reinterpret_cast<float*>(hpack + (size_t)dm.bh() * 2 * D * D);
     hipLaunchKernelGGL(attn_prep_kernel<D>, dim3(p.npad / kTile + kPackBlocks, dm.bh()), dim3(256), 0, stream,
-                       a.kbar, a.vsum, a.hsum, kcen, vbar, bias, hpack, dm.L, dm.B, dm.N, p.npad);
+                       a.kbar, a.vsum, a.hsum, kcen, vbar, hpack, dm.L, dm.B, dm.N, p.npad);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     p.kcen = kcen;
     p.vbar = vbar;
     p.hpack = hpack;
-    p.bias = bias;
   }
   if (dm.B == kTile) hipLaunchKernelGGL((attn_bf16_kernel<D, false, 1>), dim3(grid), dim3(256), 0, stream, p);
   else hipLaunchKernelGGL((attn_bf16_kernel<D, false, 2>), dim3(grid), dim3(256), 0, stream, p);
@@ -1030,7 +1043,7 @@ static hipError_t launch_attention_bf16_d(const Dims& dm, const AttnArgs& a, hip
 }
 
 // Device scratch for callers that cannot hand over a workspace (pisa_attention_static): the
-// centroid tiles, the packed hsum and the bias vector of one call.  Every device the library
+// centroid tiles and the packed hsum of one call.  Every device the library
 // runs on holds its own copy of the array until the process ends.
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
