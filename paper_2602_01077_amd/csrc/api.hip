@@ -182,6 +182,10 @@ int32_t pisa_select(const pisa_shape* shape, const double* qbar64, const double*
 }
 
 static int32_t run_attention(const Dims& dm, const AttnArgs& a, void* stream, const char* who) {
+  // the bf16 kernels address a head's K and V tiles with 32-bit byte offsets
+  if (dm.dtype == PISA_BF16 && (long long)dm.L * dm.d * 2 >= (1LL << 31))
+    return fail(PISA_UNSUPPORTED, "%s: one head of K or V must stay below 2 GiB (seq_len * head_dim * 2 = %lld bytes)",
+                who, (long long)dm.L * dm.d * 2);
   hipError_t e = dm.dtype == PISA_BF16 ? launch_attention_bf16(dm, a, (hipStream_t)stream)
                                        : launch_attention_fp32(dm, a, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(who, e);

@@ -79,6 +79,14 @@ def test_bad_shapes_are_rejected(kw, code):
                                 FAKE, 1 << 40, None) == code
 
 
+def test_heads_of_two_gib_are_refused_by_the_bf16_attention():
+    # the bf16 kernels address the tiles of one head with 32-bit byte offsets
+    lib = pisa.raw()
+    s = shape(seq_len=9_000_000, head_dim=128, dtype=pisa.PISA_BF16)
+    assert lib.dense_attention(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, None, None) == pisa.PISA_UNSUPPORTED
+    assert "2 GiB" in pisa.last_error()
+
+
 def test_null_and_range_arguments():
     lib = pisa.raw()
     s = shape()
