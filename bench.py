@@ -180,6 +180,22 @@ def main():
     note(f"{args.steps} timed steps done: {wall_ms:.3f} ms/step")
     stage = [sum(e[i].elapsed_time(e[i + 1]) for e in evs) / args.steps for i in range(3)]
 
+    # The same path through the one-call entry point (default configuration only): fewer
+    # launches, bit-identical output; timed the same way.
+    one_call_ms = None
+    if norm is None:
+        fws = torch.empty(pisa.forward_workspace_bytes(shape, k_top), dtype=torch.uint8, device=dev)
+        for _ in range(max(args.warmup, 1)):
+            pisa.forward(shape, q, k, v, k_top, out=out, workspace=fws)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            pisa.forward(shape, q, k, v, k_top, out=out, workspace=fws)
+        torch.cuda.synchronize()
+        one_call_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        note(f"pisa_forward (one call): {one_call_ms:.4f} ms/call")
+        del fws
+
     dense_ms = None
     if args.dense_steps > 0:
         dout = torch.empty_like(q)
@@ -309,6 +325,9 @@ def main():
         "dense_attention_ms": None if dense_ms is None else round(dense_ms, 3),
         "dense_attention_TFLOPs": None if dense_ms is None else round(fl_dense / (dense_ms * 1e-3) / 1e12, 1),
         "speedup_vs_dense": None if dense_ms is None else round(dense_ms / wall_ms, 3),
+        "one_call": None if one_call_ms is None else {
+            "entry": "pisa_forward", "ms": round(one_call_ms, 4), "steps": args.steps,
+            "speedup_vs_dense": None if dense_ms is None else round(dense_ms / one_call_ms, 3)},
         "speedup_vs_dense_attention_only": None if dense_ms is None else round(dense_ms / attn_ms, 3),
         "l1_error_vs_dense": None if l1_vs_dense is None else round(l1_vs_dense, 6),
         "roofline": {"kernel": "attn_bf16_kernel (pisa_attention)", "bound": "mfma",

@@ -188,6 +188,26 @@ int32_t pisa_attention_static(const pisa_shape* shape, const void* q, const void
                               const int32_t* idx, int32_t k_top,
                               void* out, float* lse, void* stream);
 
+/*
+ * Alg. 1 from its first line to its last in one call: block statistics, selection of the k_top
+ * exact blocks per query block (plain pooled-logit score, no covariance term), and the fused
+ * three-phase attention, with every intermediate kept in the workspace.  The result (out, lse)
+ * is bit for bit what pisa_block_stats + pisa_select + pisa_attention give on the same inputs.
+ * What it saves is launches, which is what short sequences pay for (the paper's remark on
+ * 4K-token inputs): on the bf16 path the statistics kernels write the attention kernel's
+ * centroid tiles and packed hsum directly (no pre-pass), and for N <= 128 blocks the reduction
+ * of the partial H sums shares the selection's launch: three launches instead of five.
+ *   q, k, v    device, shape->dtype, [batch,heads,seq_len,head_dim]
+ *   k_top      number of exact blocks per query block, 0 .. N (pisa_topk_count)
+ *   out, lse   as for pisa_attention (lse may be NULL)
+ *   workspace  device, pisa_forward_workspace_bytes(shape, k_top) bytes, 16-byte aligned,
+ *              caller-owned; contents on return: the intermediates, in no documented layout
+ * Errors as for the three calls; nothing is enqueued if validation fails.
+ */
+size_t pisa_forward_workspace_bytes(const pisa_shape* shape, int32_t k_top);   /* 0 for an invalid shape or k_top */
+int32_t pisa_forward(const pisa_shape* shape, const void* q, const void* k, const void* v, int32_t k_top,
+                     void* out, float* lse, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Preliminaries, first equation: out = softmax(s Q K^T) V with an online softmax over
  * 64-key tiles; lse as above (may be NULL).  shape->block only sets the tile walk. */
 int32_t dense_attention(const pisa_shape* shape, const void* q, const void* k, const void* v,

@@ -23,7 +23,7 @@ PISA_NORM_SPECTRAL, PISA_NORM_FROBENIUS = 0, 1
 
 EXPORTS = ("pisa_num_blocks", "pisa_topk_count", "pisa_workspace_bytes", "pisa_block_stats",
            "pisa_block_heterogeneity", "pisa_select", "pisa_attention", "pisa_attention_static",
-           "dense_attention",
+           "pisa_forward_workspace_bytes", "pisa_forward", "dense_attention",
            "pisa_probe_mfma_rate", "pisa_probe_shader_clock", "pisa_last_error")
 
 
@@ -64,6 +64,10 @@ def _load() -> ctypes.CDLL:
     lib.pisa_attention.restype = i32
     lib.pisa_attention_static.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp]
     lib.pisa_attention_static.restype = i32
+    lib.pisa_forward_workspace_bytes.argtypes = [shp, i32]
+    lib.pisa_forward_workspace_bytes.restype = sz
+    lib.pisa_forward.argtypes = [shp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
+    lib.pisa_forward.restype = i32
     lib.dense_attention.argtypes = [shp, vp, vp, vp, vp, vp, vp]
     lib.dense_attention.restype = i32
     lib.pisa_probe_mfma_rate.argtypes = [i32, vp, sz, ctypes.POINTER(ctypes.c_double), vp]
@@ -280,11 +284,35 @@ def probe_shader_clock(window_ms: float, counts: torch.Tensor) -> float:
     return hz.value
 
 
-def pisa_forward(q, k, v, block: int = 64, sparsity: float = 0.85, first_order: bool = True,
+def forward_workspace_bytes(shape: PisaShape, k_top: int) -> int:
+    return _lib.pisa_forward_workspace_bytes(ctypes.byref(shape), k_top)
+
+
+def forward(shape: PisaShape, q, k, v, k_top: int, out: Optional[torch.Tensor] = None,
+            lse: Optional[torch.Tensor] = None, want_lse: bool = False,
+            workspace: Optional[torch.Tensor] = None):
+    """pisa_forward: statistics, selection and attention in one library call (three launches on
+    the bf16 path for short sequences).  Returns (out, lse or None)."""
+    if out is None:
+        out = torch.empty_like(q)
+    if lse is None and want_lse:
+        lse = torch.empty(q.shape[:3], dtype=torch.float32, device=q.device)
+    if workspace is None:
+        workspace = torch.empty(forward_workspace_bytes(shape, k_top), dtype=torch.uint8, device=q.device)
+    _check(_lib.pisa_forward(
+        ctypes.byref(shape), _dev(q, "q"), _dev(k, "k", like=q), _dev(v, "v", like=q), k_top,
+        _dev(out, "out", like=q), _dev(lse, "lse", torch.float32),
+        _dev(workspace, "workspace", torch.uint8), workspace.numel(), _stream()))
+    return out, lse
+
+
+def forward_in_steps(q, k, v, block: int = 64, sparsity: float = 0.85, first_order: bool = True,
                  want_lse: bool = False, approximate: bool = True, covariance_aware: bool = False,
                  norm: int = PISA_NORM_SPECTRAL, eps: float = 1e-6, scale: Optional[float] = None,
                  hbar_from_stats: bool = False):
-    """The whole hot path: block_stats -> select -> attention.
+    """The whole hot path as separate library calls: block_stats -> select -> attention (the
+    variants and the covariance-aware score are options of those calls; `forward` is the one-call
+    form of the default configuration).
 
     first_order=False gives the zeroth-order variant, approximate=False plain block-sparse
     attention over the selected blocks, covariance_aware=True adds log(M_j + eps) to the

@@ -130,7 +130,7 @@ int32_t pisa_block_stats(const pisa_shape* shape, const void* q, const void* k, 
   if (workspace_bytes < need)
     return fail(PISA_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, need %zu", workspace_bytes, need);
   hipError_t e = launch_block_stats(dm, q, k, v, qbar, kbar, vsum, hsum, qbar64, kbar64,
-                                    (float*)workspace, (hipStream_t)stream);
+                                    (float*)workspace, StatsExtras{}, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail("pisa_block_stats", e);
   return PISA_OK;
 }
@@ -176,7 +176,7 @@ int32_t pisa_select(const pisa_shape* shape, const double* qbar64, const double*
   if (workspace_bytes < need)
     return fail(PISA_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, need %zu", workspace_bytes, need);
   hipError_t e = launch_select(dm, qbar64, kbar64, col_bias, k_top, idx, kth_gap, (double*)workspace,
-                               (hipStream_t)stream);
+                               nullptr, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail("pisa_select", e);
   return PISA_OK;
 }
@@ -252,6 +252,95 @@ int32_t pisa_attention_static(const pisa_shape* shape, const void* q, const void
   }
   AttnArgs a{q, k, v, kbar, vsum, hsum, idx, k_top, out, lse, false, ws};
   return run_attention(dm, a, stream, "pisa_attention_static");
+}
+
+// Layout of the workspace of pisa_forward: every intermediate of the three stages, each region
+// on a 256-byte boundary.
+namespace {
+struct ForwardCarve {
+  size_t qbar, kbar, vsum, hsum, qbar64, kbar64, idx, partial, logits, attn, total;
+};
+ForwardCarve forward_carve(const Dims& dm, int k_top) {
+  ForwardCarve c{};
+  size_t at = 0;
+  auto take = [&](size_t bytes) {
+    const size_t here = at;
+    at += (bytes + 255) & ~(size_t)255;
+    return here;
+  };
+  const size_t nd = (size_t)dm.bh() * dm.N * dm.d;
+  c.qbar = take(nd * sizeof(float));
+  c.kbar = take(nd * sizeof(float));
+  c.vsum = take(nd * sizeof(float));
+  c.hsum = take((size_t)dm.bh() * dm.d * dm.d * sizeof(float));
+  c.qbar64 = take(nd * sizeof(double));
+  c.kbar64 = take(nd * sizeof(double));
+  c.idx = take((size_t)dm.bh() * dm.N * (size_t)std::max(k_top, 1) * sizeof(int32_t));
+  c.partial = take(stats_workspace_bytes(dm));
+  c.logits = take(select_fuses_reduce(dm) ? 0 : select_workspace_bytes(dm));
+  c.attn = take(attention_workspace_bytes(dm));
+  c.total = at;
+  return c;
+}
+}  // namespace
+
+size_t pisa_forward_workspace_bytes(const pisa_shape* shape, int32_t k_top) {
+  Dims dm;
+  if (resolve(shape, &dm) != PISA_OK) return 0;
+  if (k_top < 0 || k_top > dm.N) return 0;
+  return forward_carve(dm, k_top).total;
+}
+
+int32_t pisa_forward(const pisa_shape* shape, const void* q, const void* k, const void* v, int32_t k_top,
+                     void* out, float* lse, void* workspace, size_t workspace_bytes, void* stream) {
+  Dims dm;
+  int32_t rc = resolve(shape, &dm);
+  if (rc != PISA_OK) return rc;
+  if (!q || !k || !v || !out) return fail(PISA_INVALID_ARG, "q, k, v, out must not be NULL");
+  if (k_top < 0 || k_top > dm.N)
+    return fail(PISA_INVALID_ARG, "k_top = %d outside [0, N = %d]", k_top, dm.N);
+  PISA_CHECK_ALIGN(q, k, v, out, lse, workspace);
+  if (dm.N > kMaxBlocks)
+    return fail(PISA_UNSUPPORTED, "at most %d blocks are supported (N = %d)", kMaxBlocks, dm.N);
+  const ForwardCarve c = forward_carve(dm, k_top);
+  if (!workspace) return fail(PISA_INVALID_ARG, "workspace is NULL (need %zu bytes)", c.total);
+  if (workspace_bytes < c.total)
+    return fail(PISA_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, need %zu", workspace_bytes, c.total);
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  float* qbar = reinterpret_cast<float*>(ws + c.qbar);
+  float* kbar = reinterpret_cast<float*>(ws + c.kbar);
+  float* vsum = reinterpret_cast<float*>(ws + c.vsum);
+  float* hsum = reinterpret_cast<float*>(ws + c.hsum);
+  double* qbar64 = reinterpret_cast<double*>(ws + c.qbar64);
+  double* kbar64 = reinterpret_cast<double*>(ws + c.kbar64);
+  int32_t* idx = reinterpret_cast<int32_t*>(ws + c.idx);
+  float* partial = reinterpret_cast<float*>(ws + c.partial);
+  const hipStream_t st = (hipStream_t)stream;
+
+  // bf16: the statistics launches also write what the attention kernel's pre-pass would (the
+  // centroid tiles from the statistics kernel, the packed hsum from the reduction), and on short
+  // sequences the reduction rides in the selection's single launch: three launches in all.
+  StatsExtras extra;
+  const bool fused = dm.dtype == PISA_BF16;
+  if (fused) {
+    attention_workspace_carve(dm, ws + c.attn, &extra.kcen, &extra.vbar, &extra.hpack);
+    extra.defer_reduce = k_top > 0 && select_fuses_reduce(dm);
+  }
+  hipError_t e = launch_block_stats(dm, q, k, v, qbar, kbar, vsum, hsum, qbar64, kbar64, partial, extra, st);
+  if (e != hipSuccess) return hip_fail("pisa_forward (statistics)", e);
+  if (k_top > 0) {
+    PendingReduce pending;
+    pending.partial_h = partial;
+    pending.hsum = hsum;
+    pending.hpack = extra.hpack;
+    pending.n_chunks = stats_plan(dm).n_chunks;
+    e = launch_select(dm, qbar64, kbar64, nullptr, k_top, idx, nullptr, reinterpret_cast<double*>(ws + c.logits),
+                      extra.defer_reduce ? &pending : nullptr, st);
+    if (e != hipSuccess) return hip_fail("pisa_forward (selection)", e);
+  }
+  AttnArgs a{q, k, v, kbar, vsum, hsum, k_top > 0 ? idx : nullptr, k_top, out, lse, false, ws + c.attn};
+  a.prepared = fused;
+  return run_attention(dm, a, stream, "pisa_forward (attention)");
 }
 
 int32_t dense_attention(const pisa_shape* shape, const void* q, const void* k, const void* v,

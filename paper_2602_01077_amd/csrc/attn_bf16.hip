@@ -999,6 +999,15 @@ size_t attention_workspace_bytes(const Dims& dm) {
   return (size_t)dm.bh() * (2 * npad * D * 2 + 2 * D * D * 2);
 }
 
+void attention_workspace_carve(const Dims& dm, void* workspace, void** kcen, void** vbar, void** hpack) {
+  const size_t npad = (size_t)((dm.N + kTile - 1) / kTile) * kTile;
+  const size_t tile_elems = (size_t)dm.bh() * npad * dm.d;
+  __bf16* kc = static_cast<__bf16*>(workspace);
+  *kcen = kc;
+  *vbar = kc + tile_elems;
+  *hpack = kc + 2 * tile_elems;
+}
+
 template <int D>
 static hipError_t launch_attention_bf16_d(const Dims& dm, const AttnArgs& a, hipStream_t stream) {
   PB p{};
@@ -1023,16 +1032,17 @@ static hipError_t launch_attention_bf16_d(const Dims& dm, const AttnArgs& a, hip
     return hipGetLastError();
   }
   if (a.k_top < dm.N && a.kbar) {
-    // carve the workspace: kcen | vbar | hpack
-    unsigned char* ws = static_cast<unsigned char*>(a.workspace);
-    const size_t tile_elems = (size_t)dm.bh() * p.npad * D;
-    __bf16* kcen = reinterpret_cast<__bf16*>(ws);
-    __bf16* vbar = kcen + tile_elems;
-    __bf16* hpack = vbar + tile_elems;
-    hipLaunchKernelGGL(attn_prep_kernel<D>, dim3(p.npad / kTile + kPackBlocks, dm.bh()), dim3(256), 0, stream,
-                       a.kbar, a.vsum, a.hsum, kcen, vbar, hpack, dm.L, dm.B, dm.N, p.npad);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    void *kcen_v, *vbar_v, *hpack_v;                      // kcen | vbar | hpack
+    attention_workspace_carve(dm, a.workspace, &kcen_v, &vbar_v, &hpack_v);
+    __bf16* kcen = static_cast<__bf16*>(kcen_v);
+    __bf16* vbar = static_cast<__bf16*>(vbar_v);
+    __bf16* hpack = static_cast<__bf16*>(hpack_v);
+    if (!a.prepared) {
+      hipLaunchKernelGGL(attn_prep_kernel<D>, dim3(p.npad / kTile + kPackBlocks, dm.bh()), dim3(256), 0, stream,
+                         a.kbar, a.vsum, a.hsum, kcen, vbar, hpack, dm.L, dm.B, dm.N, p.npad);
+      hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return e;
+    }
     p.kcen = kcen;
     p.vbar = vbar;
     p.hpack = hpack;

@@ -39,15 +39,35 @@ struct StatsPlan {
 };
 StatsPlan stats_plan(const Dims& dm);
 
+// What the fused forward call asks of the statistics launches beyond the plain outputs (all
+// optional; bf16 only): the centroid tiles and the packed hsum in the form the attention kernel
+// reads (they replace its pre-pass), and leaving the reduction of the partial H sums to a later
+// launch.
+struct StatsExtras {
+  void* kcen = nullptr;          // bf16 [bh][npad][d]: kbar_j
+  void* vbar = nullptr;          // bf16 [bh][npad][d]: vsum_j / B_j
+  void* hpack = nullptr;         // bf16 [bh][2][d*d]: hsum split hi / lo in operand order
+  bool defer_reduce = false;
+};
+// The reduction a deferred statistics launch left undone, for launch_select to run in its launch.
+struct PendingReduce {
+  const float* partial_h = nullptr;
+  float* hsum = nullptr;
+  void* hpack = nullptr;
+  int n_chunks = 0;
+};
+
 // Launchers (each returns hipGetLastError() after its launches).
 hipError_t launch_block_stats(const Dims& dm, const void* q, const void* k, const void* v,
                               float* qbar, float* kbar, float* vsum, float* hsum,
                               double* qbar64, double* kbar64, float* partial_h,
-                              hipStream_t stream);
+                              const StatsExtras& extra, hipStream_t stream);
 size_t select_workspace_bytes(const Dims& dm);
+// True if launch_select would take `pending` into its own (single) launch for this shape.
+bool select_fuses_reduce(const Dims& dm);
 hipError_t launch_select(const Dims& dm, const double* qbar64, const double* kbar64,
                          const double* col_bias, int k_top, int32_t* idx, float* kth_gap, double* zbuf,
-                         hipStream_t stream);
+                         const PendingReduce* pending, hipStream_t stream);
 size_t hetero_workspace_bytes(const Dims& dm);
 hipError_t launch_block_heterogeneity(const Dims& dm, const void* k, const void* v, const double* kbar64,
                                       const float* hsum, int spectral, int n_iter, double eps, double* log_m,
@@ -67,8 +87,11 @@ struct AttnArgs {
   float* lse;            // may be null
   bool dense;
   void* workspace;       // scratch for the bf16 PISA pre-pass (null for dense / fp32)
+  bool prepared = false; // the workspace already holds the pre-pass results (fused forward call)
 };
 size_t attention_workspace_bytes(const Dims& dm);
+// Where the bf16 attention pre-pass results sit inside a workspace of that size.
+void attention_workspace_carve(const Dims& dm, void* workspace, void** kcen, void** vbar, void** hpack);
 // Size of the file-scope device array behind pisa_attention_static, and its address on the
 // current device (resolved on first use, once per device).
 constexpr size_t kStaticScratchBytes = PISA_STATIC_SCRATCH_BYTES;

@@ -11,6 +11,7 @@
 #include <algorithm>
 
 #include "common.h"
+#include "reduce_h.h"
 
 namespace pisa {
 namespace {
@@ -312,17 +313,14 @@ __global__ __launch_bounds__(256) void topk_kernel(const double* __restrict__ z,
 // logits_small_kernel does and park it in LDS, then every wave selects one row.
 constexpr int kFusedMaxN = 128;
 template <int D>
-__global__ __launch_bounds__(1024) void select_small_kernel(const double* __restrict__ qbar64,
-                                                            const double* __restrict__ kbar64,
-                                                            const double* __restrict__ col_bias, int N,
-                                                            double scale, int k_top,
-                                                            int32_t* __restrict__ idx,
-                                                            float* __restrict__ kth_gap) {
+__device__ inline void select_small_body(const double* __restrict__ qbar64, const double* __restrict__ kbar64,
+                                         const double* __restrict__ col_bias, int N, double scale, int k_top,
+                                         int32_t* __restrict__ idx, float* __restrict__ kth_gap, int group,
+                                         size_t bh) {
   __shared__ double zs[16][kFusedMaxN];
   __shared__ int hist_all[16][256];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const size_t bh = blockIdx.y;
-  const int i0 = blockIdx.x * 16;
+  const int i0 = group * 16;
   const int j0 = wave * 16;
   if (j0 < N) {                            // wave-uniform
     const int r = lane & 15, kk = lane >> 4;
@@ -357,16 +355,59 @@ __global__ __launch_bounds__(1024) void select_small_kernel(const double* __rest
                             kth_gap ? kth_gap + row : nullptr, lane);
 }
 
+template <int D>
+__global__ __launch_bounds__(1024) void select_small_kernel(const double* __restrict__ qbar64,
+                                                            const double* __restrict__ kbar64,
+                                                            const double* __restrict__ col_bias, int N,
+                                                            double scale, int k_top,
+                                                            int32_t* __restrict__ idx,
+                                                            float* __restrict__ kth_gap) {
+  select_small_body<D>(qbar64, kbar64, col_bias, N, scale, k_top, idx, kth_gap, blockIdx.x, blockIdx.y);
+}
+
+// The same selection plus, in the workgroups past the first n_groups of a head, the reduction of
+// the statistics pass's partial H sums (independent work on the same inputs' statistics: one
+// launch instead of two on short sequences).
+template <int D>
+__global__ __launch_bounds__(1024) void select_small_reduce_kernel(
+    const double* __restrict__ qbar64, const double* __restrict__ kbar64, const double* __restrict__ col_bias,
+    int N, double scale, int k_top, int32_t* __restrict__ idx, float* __restrict__ kth_gap, int n_groups,
+    const float* __restrict__ partial_h, float* __restrict__ hsum, unsigned short* __restrict__ hpack,
+    int n_chunks) {
+  if ((int)blockIdx.x < n_groups) {
+    select_small_body<D>(qbar64, kbar64, col_bias, N, scale, k_top, idx, kth_gap, blockIdx.x, blockIdx.y);
+  } else {
+    const int e = ((int)blockIdx.x - n_groups) * 1024 + (int)threadIdx.x;
+    if (e < D * D) reduce_h_element(partial_h, hsum, hpack, n_chunks, D, blockIdx.y, e);
+  }
+}
+
 }  // namespace
 
 size_t select_workspace_bytes(const Dims& dm) {
   return (size_t)dm.bh() * dm.N * dm.N * sizeof(double);
 }
 
+bool select_fuses_reduce(const Dims& dm) { return dm.N <= kFusedMaxN; }
+
 hipError_t launch_select(const Dims& dm, const double* qbar64, const double* kbar64,
                          const double* col_bias, int k_top, int32_t* idx, float* kth_gap, double* zbuf,
-                         hipStream_t stream) {
+                         const PendingReduce* pending, hipStream_t stream) {
   const int nt = (dm.N + kZT - 1) / kZT;
+  if (pending && !select_fuses_reduce(dm)) return hipErrorInvalidValue;   // the caller checks first
+  if (dm.N <= kFusedMaxN && pending) {                    // selection and H reduction in one launch
+    const int n_groups = (dm.N + 15) / 16;
+    const dim3 fgrid(n_groups + (dm.d * dm.d + 1023) / 1024, dm.bh());
+    if (dm.d == 64)
+      hipLaunchKernelGGL(select_small_reduce_kernel<64>, fgrid, dim3(1024), 0, stream, qbar64, kbar64, col_bias,
+                         dm.N, (double)dm.scale, k_top, idx, kth_gap, n_groups, pending->partial_h,
+                         pending->hsum, (unsigned short*)pending->hpack, pending->n_chunks);
+    else
+      hipLaunchKernelGGL(select_small_reduce_kernel<128>, fgrid, dim3(1024), 0, stream, qbar64, kbar64, col_bias,
+                         dm.N, (double)dm.scale, k_top, idx, kth_gap, n_groups, pending->partial_h,
+                         pending->hsum, (unsigned short*)pending->hpack, pending->n_chunks);
+    return hipGetLastError();
+  }
   if (dm.N <= kFusedMaxN) {                               // one launch for short sequences
     const dim3 fgrid((dm.N + 15) / 16, dm.bh());
     if (dm.d == 64)

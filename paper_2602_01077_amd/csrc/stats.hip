@@ -7,6 +7,7 @@
 // d x d matrix; a second kernel adds the partials in chunk order, so hsum is
 // bit-identical from run to run.
 #include "common.h"
+#include "reduce_h.h"
 
 namespace pisa {
 namespace {
@@ -119,24 +120,14 @@ __global__ __launch_bounds__(256) void stats_kernel(
     for (int b = 0; b < R; ++b) ph[(size_t)(ta * R + a) * D + tb * R + b] = h[a][b];
 }
 
-// hsum[bh][e] = sum over chunks (in chunk order) of partial_h[bh][chunk][e].
+// hsum (and, if asked for, its packed bf16 split) from the per-chunk partial sums: one thread
+// per matrix element.
 __global__ __launch_bounds__(256) void reduce_h_kernel(const float* __restrict__ partial_h,
-                                                       float* __restrict__ hsum, int n_chunks, int dd) {
-  const size_t bh = blockIdx.y;
+                                                       float* __restrict__ hsum,
+                                                       unsigned short* __restrict__ hpack, int n_chunks, int D) {
   const int e = blockIdx.x * 256 + threadIdx.x;
-  if (e >= dd) return;
-  const float* p = partial_h + bh * n_chunks * (size_t)dd + e;
-  float acc = 0.f;
-  int c = 0;
-  for (; c + 8 <= n_chunks; c += 8) {         // eight loads in flight, added in chunk order
-    float x[8];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) x[u] = p[(size_t)(c + u) * dd];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) acc += x[u];
-  }
-  for (; c < n_chunks; ++c) acc += p[(size_t)c * dd];
-  hsum[bh * dd + e] = acc;
+  if (e >= D * D) return;
+  reduce_h_element(partial_h, hsum, hpack, n_chunks, D, blockIdx.y, e);
 }
 
 }  // namespace
@@ -144,12 +135,12 @@ __global__ __launch_bounds__(256) void reduce_h_kernel(const float* __restrict__
 hipError_t launch_block_stats_bf16(const Dims& dm, const void* q, const void* k, const void* v,
                                        float* qbar, float* kbar, float* vsum,
                                        double* qbar64, double* kbar64, float* partial_h,
-                                       const StatsPlan& plan, hipStream_t stream);
+                                       void* kcen, void* vbar, const StatsPlan& plan, hipStream_t stream);
 
 hipError_t launch_block_stats(const Dims& dm, const void* q, const void* k, const void* v,
                               float* qbar, float* kbar, float* vsum, float* hsum,
                               double* qbar64, double* kbar64, float* partial_h,
-                              hipStream_t stream) {
+                              const StatsExtras& extra, hipStream_t stream) {
   const StatsPlan plan = stats_plan(dm);
   dim3 grid(plan.n_chunks, dm.bh());
 #define PISA_STATS(T, DD)                                                                          \
@@ -158,7 +149,7 @@ hipError_t launch_block_stats(const Dims& dm, const void* q, const void* k, cons
                      plan.chunk_blocks, plan.n_chunks)
   if (dm.dtype == PISA_BF16) {
     hipError_t e = launch_block_stats_bf16(dm, q, k, v, qbar, kbar, vsum, qbar64, kbar64,
-                                           partial_h, plan, stream);
+                                           partial_h, extra.kcen, extra.vbar, plan, stream);
     if (e != hipSuccess) return e;
   } else if (dm.d == 64) {
     PISA_STATS(float, 64);
@@ -168,9 +159,10 @@ hipError_t launch_block_stats(const Dims& dm, const void* q, const void* k, cons
 #undef PISA_STATS
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  if (extra.defer_reduce) return hipSuccess;   // the caller reduces the partial sums in a later launch
   const int dd = dm.d * dm.d;
   hipLaunchKernelGGL(reduce_h_kernel, dim3((dd + 255) / 256, dm.bh()), dim3(256), 0, stream,
-                     partial_h, hsum, plan.n_chunks, dd);
+                     partial_h, hsum, (unsigned short*)extra.hpack, plan.n_chunks, dm.d);
   return hipGetLastError();
 }
 

@@ -78,6 +78,7 @@ __global__ __launch_bounds__(256, 2) void stats_bf16_kernel(
     const unsigned int* __restrict__ q, const unsigned int* __restrict__ k, const unsigned int* __restrict__ v,
     float* __restrict__ qbar, float* __restrict__ kbar, float* __restrict__ vsum,
     double* __restrict__ qbar64, double* __restrict__ kbar64, float* __restrict__ partial_h,
+    unsigned short* __restrict__ kcen, unsigned short* __restrict__ vbar, int npad,
     int L, int N, int chunk_blocks, int n_chunks) {
   constexpr int B = TPB * kTile;
   constexpr int TILEB = kTile * 2 * D;
@@ -114,6 +115,23 @@ __global__ __launch_bounds__(256, 2) void stats_bf16_kernel(
   f32x16 acc[NB];
 #pragma unroll
   for (int bt = 0; bt < NB; ++bt) acc[bt] = (f32x16){0};
+
+  // Optional second form of the block outputs, for the attention kernel's centroid phase: the
+  // key mean and the value mean of block j as bf16 rows of tiles [bh][npad][D] (the fp32
+  // values just written, rounded to nearest even; rows N .. npad - 1 are zero).  Called by
+  // the threads tid < D.
+  auto centroid_rows = [&](int j, float kmean, float vs, int rows_in_block) {
+    if (!kcen) return;
+    const size_t o = (bh * (size_t)npad + j) * D + tid;
+    kcen[o] = (unsigned short)pack_bf16(kmean, 0.f);
+    vbar[o] = (unsigned short)pack_bf16(vs * (1.f / (float)rows_in_block), 0.f);
+    if (j == N - 1)
+      for (int jj = N; jj < npad; ++jj) {
+        const size_t oz = (bh * (size_t)npad + jj) * D + tid;
+        kcen[oz] = 0;
+        vbar[oz] = 0;
+      }
+  };
 
   // This wave's 16 rows of one 64-token sub-block, one channel pair per lane.  Rows past the
   // end repeat the last valid row (the users mask them), so the loads carry no conditions.
@@ -195,6 +213,7 @@ __global__ __launch_bounds__(256, 2) void stats_bf16_kernel(
           vsum[o] = (float)sv;
           if (qbar64) qbar64[o] = qm;
           if (kbar64) kbar64[o] = cm;
+          centroid_rows(j, (float)cm, (float)sv, rows);
         } else {
           tot[0][tid] = sub == 0 ? sq : tot[0][tid] + sq;
           tot[1][tid] = sub == 0 ? sk : tot[1][tid] + sk;
@@ -254,6 +273,7 @@ __global__ __launch_bounds__(256, 2) void stats_bf16_kernel(
         vsum[o] = (float)tot[2][tid];
         if (qbar64) qbar64[o] = qm;
         if (kbar64) kbar64[o] = km;
+        centroid_rows(j, (float)km, (float)tot[2][tid], block_rows);
         for (int sub = 0; sub < n_sub; ++sub) dks[sub][tid] = (float)(csub[sub][tid] - km);
       }
       __syncthreads();
@@ -283,12 +303,14 @@ __global__ __launch_bounds__(256, 2) void stats_bf16_kernel(
 hipError_t launch_block_stats_bf16(const Dims& dm, const void* q, const void* k, const void* v,
                                    float* qbar, float* kbar, float* vsum,
                                    double* qbar64, double* kbar64, float* partial_h,
-                                   const StatsPlan& plan, hipStream_t stream) {
+                                   void* kcen, void* vbar, const StatsPlan& plan, hipStream_t stream) {
+  const int npad = ((dm.N + kTile - 1) / kTile) * kTile;
   const dim3 grid(plan.n_chunks, dm.bh());
 #define PISA_STATS_BF16(DD, TPB)                                                                           \
   hipLaunchKernelGGL((stats_bf16_kernel<DD, TPB>), grid, dim3(256), 0, stream, (const unsigned int*)q,     \
                      (const unsigned int*)k, (const unsigned int*)v, qbar, kbar, vsum, qbar64, kbar64,     \
-                     partial_h, dm.L, dm.N, plan.chunk_blocks, plan.n_chunks)
+                     partial_h, (unsigned short*)kcen, (unsigned short*)vbar, npad, dm.L, dm.N,                \
+                     plan.chunk_blocks, plan.n_chunks)
   if (dm.d == 128 && dm.B == kTile) PISA_STATS_BF16(128, 1);
   else if (dm.d == 128) PISA_STATS_BF16(128, 2);
   else if (dm.B == kTile) PISA_STATS_BF16(64, 1);

@@ -48,7 +48,7 @@ def _error_row(w, q, k, v, r, row):
         if name == "keep_or_drop" and pisa.topk_count(n, r) == 0:
             row[name] = None
             continue
-        out = pisa.pisa_forward(q, k, v, w.block, r, **kw)["out"]
+        out = pisa.forward_in_steps(q, k, v, w.block, r, **kw)["out"]
         row[name] = (out.float() - dense.float()).abs().sum().item() / den
     print(json.dumps(row), flush=True)
 
@@ -85,7 +85,7 @@ def error_study(args):
             if name == "keep_or_drop" and pisa.topk_count(pisa.num_blocks(w.seq_len, w.block), r) == 0:
                 row[name] = None
                 continue
-            out = pisa.pisa_forward(q, k, v, w.block, r, **kw)["out"]
+            out = pisa.forward_in_steps(q, k, v, w.block, r, **kw)["out"]
             row[name] = (out.float() - dense.float()).abs().sum().item() / den
         print(json.dumps(row), flush=True)
 
@@ -113,8 +113,12 @@ def speed_study(args):
                                workspace=ws)
 
             ms = _time_ms(path, args.iters)
+            fws = torch.empty(pisa.forward_workspace_bytes(shape, k_top), dtype=torch.uint8, device=dev)
+            one_ms = _time_ms(lambda: pisa.forward(shape, q, k, v, k_top, out=out, workspace=fws), args.iters)
+            del fws
             row = {"shape": "B2-H16-D128", "seq_len": L, "density": round(1 - r, 4), "k_top": k_top,
-                   "dense_ms": round(dense_ms, 4), "pisa_ms": round(ms, 4), "speedup": round(dense_ms / ms, 3)}
+                   "dense_ms": round(dense_ms, 4), "pisa_ms": round(ms, 4), "speedup": round(dense_ms / ms, 3),
+                   "one_call_ms": round(one_ms, 4), "one_call_speedup": round(dense_ms / one_ms, 3)}
             if args.graph:                                   # the same six launches replayed from a HIP graph
                 graph = torch.cuda.CUDAGraph()
                 side = torch.cuda.Stream()

@@ -79,6 +79,23 @@ def test_bad_shapes_are_rejected(kw, code):
                                 FAKE, 1 << 40, None) == code
 
 
+def test_forward_validation():
+    lib = pisa.raw()
+    s = shape(dtype=pisa.PISA_BF16, head_dim=128)
+    need = pisa.forward_workspace_bytes(s, 4)
+    # at least the intermediates of the three stages: fp32 and fp64 block means, the index rows
+    assert need >= 2 * 16 * 128 * (3 * 4 + 2 * 8) + 2 * 16 * 4 * 4
+    assert pisa.forward_workspace_bytes(s, 17) == 0 and pisa.forward_workspace_bytes(s, -1) == 0
+    assert pisa.forward_workspace_bytes(shape(head_dim=96), 4) == 0
+    assert lib.pisa_forward(ctypes.byref(s), FAKE, FAKE, FAKE, 4, FAKE, None, None, 0, None) == pisa.PISA_INVALID_ARG
+    assert lib.pisa_forward(ctypes.byref(s), FAKE, FAKE, FAKE, 4, FAKE, None, FAKE, need - 1, None) \
+        == pisa.PISA_WORKSPACE_TOO_SMALL
+    assert lib.pisa_forward(ctypes.byref(s), FAKE, FAKE, FAKE, 17, FAKE, None, FAKE, 1 << 40, None) \
+        == pisa.PISA_INVALID_ARG
+    assert lib.pisa_forward(ctypes.byref(s), None, FAKE, FAKE, 4, FAKE, None, FAKE, 1 << 40, None) \
+        == pisa.PISA_INVALID_ARG
+
+
 def test_heads_of_two_gib_are_refused_by_the_bf16_attention():
     # the bf16 kernels address the tiles of one head with 32-bit byte offsets
     lib = pisa.raw()

@@ -67,7 +67,7 @@ def run_full_case(pisa, w, blocks_per_head=None, heads=None, first_order=True, a
     the listed heads against the oracle (all query blocks unless blocks_per_head)."""
     q, k, v = make_qkv(w, device="cpu")
     qd, kd, vd = q.to(DEV), k.to(DEV), v.to(DEV)
-    res = pisa.pisa_forward(qd, kd, vd, w.block, w.sparsity, first_order=first_order, want_lse=True,
+    res = pisa.forward_in_steps(qd, kd, vd, w.block, w.sparsity, first_order=first_order, want_lse=True,
                             approximate=approximate)
     dense, dense_lse = pisa.dense_attention(qd, kd, vd, w.block, want_lse=True)
     torch.cuda.synchronize()
@@ -208,7 +208,7 @@ def test_batch_of_two(lib, dtype, d):
     scale = lib.resolved_scale(d)
     parts = [make_qkv(w, batch_index=b) for b in range(2)]
     q, k, v = (torch.cat([p[i] for p in parts], dim=0) for i in range(3))
-    res = lib.pisa_forward(q.to(DEV), k.to(DEV), v.to(DEV), w.block, w.sparsity, want_lse=True)
+    res = lib.forward_in_steps(q.to(DEV), k.to(DEV), v.to(DEV), w.block, w.sparsity, want_lse=True)
     torch.cuda.synchronize()
     for b in range(2):
         for h in range(w.heads):
@@ -228,7 +228,7 @@ def test_all_blocks_selected_is_bitwise_dense(lib, dtype, d, B):
     """At r = 0 the PISA kernel must return exactly what the dense kernel returns."""
     w = WORKLOADS["tiny"].with_(name="r0", heads=2, seq_len=1100, head_dim=d, dtype=dtype, block=B, sparsity=0.0)
     q, k, v = (x.to(DEV) for x in make_qkv(w))
-    res = lib.pisa_forward(q, k, v, B, 0.0, want_lse=True)
+    res = lib.forward_in_steps(q, k, v, B, 0.0, want_lse=True)
     dense, lse = lib.dense_attention(q, k, v, B, want_lse=True)
     torch.cuda.synchronize()
     assert res["k_top"] == wl_blocks(w)
@@ -289,7 +289,7 @@ def test_covariance_aware_selection(lib, dtype, d, B, L):
             ref2, gref2 = po.select(st["qbar"], st["kbar"], scale, k_top, col_bias=np.log(M + 1e-6))
             check_select(idx[0, h].cpu().numpy(), None, ref2, gref2, N, where=f" cov {kind} head {h} (Hbar from hsum)")
     # end to end with the covariance-aware score
-    res = lib.pisa_forward(qd, kd, vd, B, w.sparsity, covariance_aware=True, norm=lib.PISA_NORM_FROBENIUS)
+    res = lib.forward_in_steps(qd, kd, vd, B, w.sparsity, covariance_aware=True, norm=lib.PISA_NORM_FROBENIUS)
     torch.cuda.synchronize()
     for h in range(w.heads):
         Q, K, V = head_np(q, 0, h), head_np(k, 0, h), head_np(v, 0, h)
@@ -353,7 +353,7 @@ def test_custom_softmax_scale(lib, dtype, d, scale):
     q, k, v = make_qkv(w, device="cpu")
     qd, kd, vd = q.to(DEV), k.to(DEV), v.to(DEV)
     s32 = lib.resolved_scale(d, scale)
-    res = lib.pisa_forward(qd, kd, vd, w.block, w.sparsity, want_lse=True, scale=scale)
+    res = lib.forward_in_steps(qd, kd, vd, w.block, w.sparsity, want_lse=True, scale=scale)
     dense, _ = lib.dense_attention(qd, kd, vd, w.block, scale=scale)
     torch.cuda.synchronize()
     N, k_top = wl_blocks(w), wl_topk(w)
@@ -392,7 +392,7 @@ def test_runaway_maximum(lib, direction):
     qd, kd, vd = q.to(DEV), k.to(DEV), v.to(DEV)
     scale = lib.resolved_scale(d)
     dense, dense_lse = lib.dense_attention(qd, kd, vd, B, want_lse=True)
-    res = lib.pisa_forward(qd, kd, vd, B, w.sparsity, want_lse=True)
+    res = lib.forward_in_steps(qd, kd, vd, B, w.sparsity, want_lse=True)
     torch.cuda.synchronize()
     assert torch.isfinite(dense.float()).all() and torch.isfinite(res["out"].float()).all()
     blocks = [0, 1, 17, 35]
@@ -562,7 +562,7 @@ def test_video_configs_sampled(lib, name):
     w = WORKLOADS[name]
     scale = lib.resolved_scale(w.head_dim)
     q, k, v = make_qkv(w, device=DEV)
-    res = lib.pisa_forward(q, k, v, w.block, w.sparsity, want_lse=True)
+    res = lib.forward_in_steps(q, k, v, w.block, w.sparsity, want_lse=True)
     dense, _ = lib.dense_attention(q, k, v, w.block)
     torch.cuda.synchronize()
     N, k_top = wl_blocks(w), wl_topk(w)
@@ -602,7 +602,7 @@ def test_maximum_block_count(lib, block, L):
     assert wl_blocks(w) == 4096
     scale = lib.resolved_scale(w.head_dim)
     q, k, v = make_qkv(w, device=DEV)
-    res = lib.pisa_forward(q, k, v, block, w.sparsity, want_lse=True)
+    res = lib.forward_in_steps(q, k, v, block, w.sparsity, want_lse=True)
     dense, _ = lib.dense_attention(q, k, v, block)
     torch.cuda.synchronize()
     N, k_top = wl_blocks(w), wl_topk(w)
@@ -631,7 +631,7 @@ def test_wan_sweep_sampled(lib, block, r):
     heads = [0, 7, 13, 19, 22, 28, 33, 39]
     scale = lib.resolved_scale(w.head_dim)
     q, k, v = make_qkv(w, device=DEV, heads=heads)
-    res = lib.pisa_forward(q, k, v, block, r)
+    res = lib.forward_in_steps(q, k, v, block, r)
     torch.cuda.synchronize()
     N, k_top = wl_blocks(w), wl_topk(w)
     assert res["k_top"] == k_top
@@ -668,3 +668,66 @@ def test_shader_clock_probe(lib):
     assert 0.9 * 2.0e-3 <= ticks / hz <= 5.0e-3, (ticks, hz)          # about the 2 ms asked for
     ghz = cyc / ticks * hz / 1e9
     assert 0.05 <= ghz <= 3.0, ghz
+
+
+@pytest.mark.parametrize("dtype,d,B,L,heads,r", [
+    ("bf16", 128, 64, 4608, 6, 0.85),       # FLUX-sized rows: N = 72, the three-launch form
+    ("bf16", 128, 64, 1500, 2, 0.7),        # ragged last block
+    ("bf16", 128, 128, 1400, 2, 0.6),       # block 128, ragged
+    ("bf16", 64, 64, 1300, 3, 0.75),        # head_dim 64
+    ("bf16", 64, 128, 2048, 2, 0.5),
+    ("bf16", 128, 64, 64 * 200, 2, 0.9),    # N = 200 > 128: selection in two launches, reduction on its own
+    ("bf16", 128, 64, 640, 2, 1.0),         # k_top = 0: centroids only
+    ("bf16", 128, 64, 640, 2, 0.0),         # k_top = N: every block exact
+    ("fp32", 64, 64, 1024, 2, 0.75),        # fp32 path: the three stages in a row
+])
+def test_forward_in_one_call_equals_the_three_calls(lib, dtype, d, B, L, heads, r):
+    """pisa_forward against pisa_block_stats + pisa_select + pisa_attention on the same inputs: bit for bit
+    (the three-call path is the one compared with the oracle everywhere else), twice in a row on one
+    workspace filled with NaN patterns first."""
+    w = WORKLOADS["tiny"].with_(name="one-call", heads=heads, seq_len=L, head_dim=d, dtype=dtype, block=B,
+                                sparsity=r, seed=71)
+    q, k, v = (x.to(DEV) for x in make_qkv(w))
+    ref = lib.forward_in_steps(q, k, v, B, r, want_lse=True)
+    shape = lib.make_shape(q, B)
+    k_top = ref["k_top"]
+    need = lib.forward_workspace_bytes(shape, k_top)
+    assert need > 0
+    ws = torch.full((need,), 0xFF, dtype=torch.uint8, device=DEV)
+    for _ in range(2):
+        out = torch.full_like(q, float("nan"))
+        lse = torch.full(q.shape[:3], float("nan"), dtype=torch.float32, device=DEV)
+        lib.forward(shape, q, k, v, k_top, out=out, lse=lse, workspace=ws)
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16 if dtype == "bf16" else torch.int32),
+                           ref["out"].view(torch.int16 if dtype == "bf16" else torch.int32))
+        assert torch.equal(lse, ref["lse"])
+
+
+def test_forward_in_one_call_against_the_oracle(lib):
+    """The one-call entry point compared with the oracle directly (FLUX-sized heads, bf16)."""
+    w = WORKLOADS["flux"].with_(name="one-call-oracle", heads=2, seed=72)
+    scale = lib.resolved_scale(w.head_dim)
+    q, k, v = make_qkv(w)
+    qd, kd, vd = q.to(DEV), k.to(DEV), v.to(DEV)
+    shape = lib.make_shape(qd, w.block)
+    k_top = wl_topk(w)
+    out, _ = lib.forward(shape, qd, kd, vd, k_top)
+    torch.cuda.synchronize()
+    for h in range(w.heads):
+        Q, K, V = head_np(q, 0, h), head_np(k, 0, h), head_np(v, 0, h)
+        st = po.block_stats(Q, K, V, w.block)
+        idx_ref, _ = po.select(st["qbar"], st["kbar"], scale, k_top)
+        ref, _ = po.attention_head(Q, K, V, w.block, idx_ref, scale, "hybrid", stats=st)
+        rel, cos = row_errors(out[0, h].float().cpu().numpy(), ref)
+        assert rel <= TOL[q.dtype] and cos >= COS_MIN, (h, rel, cos)
+
+
+def test_forward_rejects_a_small_workspace(lib):
+    w = WORKLOADS["tiny"]
+    q, k, v = (x.to(DEV) for x in make_qkv(w))
+    shape = lib.make_shape(q, w.block)
+    ws = torch.empty(1024, dtype=torch.uint8, device=DEV)
+    with pytest.raises(lib.PisaError) as e:
+        lib.forward(shape, q, k, v, 4, workspace=ws)
+    assert e.value.code == lib.PISA_WORKSPACE_TOO_SMALL
