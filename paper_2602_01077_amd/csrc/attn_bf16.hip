@@ -3,7 +3,7 @@
 //
 // Workgroup = 4 wavefronts = 128 query rows (two adjacent 64-row query blocks, or one
 // 128-row block); wave w owns rows 32w..32w+31 and sees every key of a staged tile.
-// Two workgroups fit a CU (2 x 66 KB LDS at D = 128, <= 256 VGPRs), so barrier stalls of one
+// Two workgroups fit a CU (2 x 75 KB LDS at D = 128, <= 256 VGPRs), so barrier stalls of one
 // are covered by the other.
 //
 // Everything is computed transposed with v_mfma_f32_32x32x16_bf16:
@@ -22,18 +22,22 @@
 // chunk index with another (conflict-free ds_read_b64_tr_b16, which hands a 16-lane group a
 // 16-channel x 4-key transposed fragment, i.e. the V^T operand straight from row-major V).
 //
-// Tile loop: software-pipelined (K one tile ahead of V; S^T(t+1) issued in the same
-// straight-line block as the exponentials of tile t, with the next tiles' loads between its
-// MFMAs), and the running maximum is lazy: a full exact tile is exponentiated against the
-// maximum as it stands and the exact step (new maximum, rescale) runs only when a tile sum
+// Tile loop: one barrier per trip; after it the loads of K(t+2) and V(t+1) go out, then the
+// softmax of trip t, O^T += V(t)^T P(t)^T, and S^T(t+1) into the score registers the softmax
+// has just consumed.  The running maximum is lazy: a full exact tile is exponentiated against
+// the maximum as it stands and the exact step (new maximum, rescale) runs only when a tile sum
 // nears overflow or on a wave's first tile.
 //
-// PISA, block 64: the two query blocks of a workgroup walk the UNION of their selected
-// key blocks in ascending order (bit scan over two LDS bitmasks); a tile selected by only
-// one block is skipped by the other block's waves.  Every shared tile halves the L2->LDS
-// traffic per flop.  Phase 2 streams bf16 centroid tiles prepared by a small pre-pass
-// (kbar_j rounded to bf16, the precision the keys themselves arrive in; vsum_j / B_j;
-// log2 B_j), Phase 3 multiplies by the pre-packed hi/lo split of hsum.
+// PISA, block 64: the index rows of the workgroup's two query blocks are merged into a trip
+// list in LDS.  A tile both blocks selected is one full trip; the tiles only one block selected
+// are paired (i-th of the first block with i-th of the second) and each pair is walked as two
+// split trips in which the stage holds 32 keys of either tile and each block's waves take their
+// half, so no wave sits a trip out and every unshared tile is still loaded once.  A workgroup
+// whose rows coincide runs the loop without the half guards (the dense kernel's code).
+// Phase 2 streams bf16 centroid tiles (kbar_j rounded to bf16, the precision the keys
+// themselves arrive in; vsum_j / B_j), written by a small pre-pass or, in the one-call entry
+// point, by the statistics kernels; Phase 3 multiplies by the pre-packed hi/lo split of hsum,
+// staged through LDS once per workgroup.
 #include <mutex>
 #include <type_traits>
 
