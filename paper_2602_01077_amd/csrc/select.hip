@@ -377,8 +377,10 @@ __global__ __launch_bounds__(1024) void select_small_reduce_kernel(
   if ((int)blockIdx.x < n_groups) {
     select_small_body<D>(qbar64, kbar64, col_bias, N, scale, k_top, idx, kth_gap, blockIdx.x, blockIdx.y);
   } else {
-    const int e = ((int)blockIdx.x - n_groups) * 1024 + (int)threadIdx.x;
-    if (e < D * D) reduce_h_element(partial_h, hsum, hpack, n_chunks, D, blockIdx.y, e);
+    // four elements per thread, 1024 apart (consecutive threads stay on consecutive addresses):
+    // few workgroups, so that the whole launch is resident at once
+    const int e0 = ((int)blockIdx.x - n_groups) * 4096 + (int)threadIdx.x;
+    reduce_h_elements<4>(partial_h, hsum, hpack, n_chunks, D, blockIdx.y, e0, 1024);
   }
 }
 
@@ -397,7 +399,7 @@ hipError_t launch_select(const Dims& dm, const double* qbar64, const double* kba
   if (pending && !select_fuses_reduce(dm)) return hipErrorInvalidValue;   // the caller checks first
   if (dm.N <= kFusedMaxN && pending) {                    // selection and H reduction in one launch
     const int n_groups = (dm.N + 15) / 16;
-    const dim3 fgrid(n_groups + (dm.d * dm.d + 1023) / 1024, dm.bh());
+    const dim3 fgrid(n_groups + (dm.d * dm.d + 4095) / 4096, dm.bh());
     if (dm.d == 64)
       hipLaunchKernelGGL(select_small_reduce_kernel<64>, fgrid, dim3(1024), 0, stream, qbar64, kbar64, col_bias,
                          dm.N, (double)dm.scale, k_top, idx, kth_gap, n_groups, pending->partial_h,
