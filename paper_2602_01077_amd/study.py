@@ -54,17 +54,30 @@ def _error_row(w, q, k, v, r, row):
 
 
 def error_vs_length(args):
-    """Fixed density, growing length (the paper's second error plot: 20 % density)."""
-    base = WORKLOADS["wan"]
+    """Fixed density, growing length (the paper's second error plot: 20 % density).  --style wan: the
+    first L tokens of a video-shaped latent grid; --style flux: 512 text tokens and a square image
+    grid of about L latents."""
     r = args.sparsity[0]
-    heads = list(range(0, base.heads, max(1, base.heads // args.heads)))[: args.heads]
     for L in args.lengths:
-        frames = -(-L // (45 * 80))
-        w = base.with_(name=f"wan-L{L}", seq_len=L, grid=(frames, 45, 80))
-        # the generator lays the field over whole frames; the sequence is its first L tokens
-        full = w.with_(seq_len=frames * 45 * 80)
-        q, k, v = (x[:, :, :L].contiguous() for x in make_qkv(full, device="cuda:0", heads=heads))
-        _error_row(w, q, k, v, r, {"workload": w.name, "heads": len(heads), "seq_len": L, "block": w.block,
+        if args.style == "flux":
+            base = WORKLOADS["flux"]
+            g = max(8, int(round(L ** 0.5)))
+            w = base.with_(name=f"flux-{g}x{g}", seq_len=512 + g * g, grid=(g, g),
+                           block_offset_std=args.block_offset_std, value_field=args.value_field)
+            heads = list(range(0, base.heads, max(1, base.heads // args.heads)))[: args.heads]
+            q, k, v = make_qkv(w, device="cuda:0", heads=heads)
+        else:
+            base = WORKLOADS["wan"]
+            heads = list(range(0, base.heads, max(1, base.heads // args.heads)))[: args.heads]
+            frames = -(-L // (45 * 80))
+            w = base.with_(name=f"wan-L{L}" + ("-clustered" if args.block_offset_std > 0 else "")
+                           + ("-vfield" if args.value_field > 0 else ""), seq_len=L,
+                           grid=(frames, 45, 80), block_offset_std=args.block_offset_std,
+                           value_field=args.value_field)
+            # the generator lays the field over whole frames; the sequence is its first L tokens
+            full = w.with_(seq_len=frames * 45 * 80)
+            q, k, v = (x[:, :, :L].contiguous() for x in make_qkv(full, device="cuda:0", heads=heads))
+        _error_row(w, q, k, v, r, {"workload": w.name, "heads": len(heads), "seq_len": w.seq_len, "block": w.block,
                                    "sparsity": r, "density": round(1 - r, 4)})
 
 
@@ -138,6 +151,15 @@ def main():
     e.add_argument("--workload", default="wan", choices=list(WORKLOADS))
     e.add_argument("--heads", type=int, default=8)
     e.add_argument("--sparsity", type=float, nargs="+", default=[0.5, 0.75, 0.8, 0.85, 0.875, 0.9, 0.95])
+    e.add_argument("--block-offset-std", type=float, default=0.0,
+                   help="with --lengths: add one N(0, std^2) offset per 64-token block to q and k (the tiny "
+                        "configuration's clustered keys), so that the blocks differ and the approximation terms show")
+    e.add_argument("--style", choices=["wan", "flux"], default="wan",
+                   help="with --lengths: which model's token layout the sequences of growing length follow")
+    e.add_argument("--value-field", type=float, default=0.0,
+                   help="with --lengths: v = N(0,1) + this x a smooth field of its own over the latent grid "
+                        "(values that vary slowly with position, as real activations do; the default values are "
+                        "pure noise, whose block means carry nothing for the approximation terms to recover)")
     e.add_argument("--lengths", type=int, nargs="+", default=None,
                    help="sweep the sequence length at the first --sparsity instead of sweeping the density")
     s = sub.add_parser("speed")

@@ -80,7 +80,7 @@ def _normal(key: int, n: int, device) -> torch.Tensor:
 
 
 # tensor ids of the independent streams
-_TID_Q, _TID_K, _TID_V, _TID_FIELD, _TID_OFFSET = 1, 2, 3, 4, 5
+_TID_Q, _TID_K, _TID_V, _TID_FIELD, _TID_OFFSET, _TID_VFIELD = 1, 2, 3, 4, 5, 6
 
 
 @dataclass(frozen=True)
@@ -100,6 +100,7 @@ class Workload:
     block_offset_std: float = 0.0   # config "tiny": shared per-block offset on q and k
     field_terms: int = 4
     field_fmax: float = 0.2
+    value_field: float = 0.0        # > 0: v also carries a smooth field of its own, scaled by this (error studies)
 
     def with_(self, **kw) -> "Workload":
         d = dict(self.__dict__)
@@ -126,7 +127,7 @@ def torch_dtype(name: str) -> torch.dtype:
     return {"fp32": torch.float32, "bf16": torch.bfloat16}[name]
 
 
-def _field(w: Workload, head: int, device) -> Optional[torch.Tensor]:
+def _field(w: Workload, head: int, device, tid: int = _TID_FIELD) -> Optional[torch.Tensor]:
     """[L, d] fp64 smooth field for one head (zero on non-grid tokens), or None."""
     if w.grid is None:
         return None
@@ -136,7 +137,7 @@ def _field(w: Workload, head: int, device) -> Optional[torch.Tensor]:
         n_grid *= g
     assert w.grid_start + n_grid <= L
     naxes = len(w.grid)
-    key = _stream_key(w.seed, _TID_FIELD, head)
+    key = _stream_key(w.seed, tid, head)
     # per (channel, term): naxes frequencies then one phase
     per = naxes + 1
     cnt = torch.arange(d * w.field_terms * per, dtype=torch.int64, device=device)
@@ -187,6 +188,7 @@ def make_qkv(w: Workload, device="cpu", heads: Optional[Sequence[int]] = None,
         hh = h + batch_index * w.heads
         shared = _field(w, hh, device)
         off = _block_offsets(w, hh, device)
+        vfield = _field(w, hh, device, _TID_VFIELD) if w.value_field > 0.0 else None
         for tid, dst in ((_TID_Q, q), (_TID_K, k), (_TID_V, v)):
             x = _normal(_stream_key(w.seed, tid, hh), L * d, device).reshape(L, d)
             if tid != _TID_V:
@@ -194,6 +196,8 @@ def make_qkv(w: Workload, device="cpu", heads: Optional[Sequence[int]] = None,
                     x = x + shared
                 if off is not None:
                     x = x + off
+            elif vfield is not None:
+                x = x + w.value_field * vfield
             dst[0, slot] = x.to(dt)
     return q, k, v
 
