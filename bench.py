@@ -101,7 +101,7 @@ def main():
     ap.add_argument("--dense-steps", type=int, default=3, help="timed dense_attention calls (0 = skip)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-probe", action="store_true", help="skip the measured-peak probes (MFMA loop, 1 GiB copy)")
-    ap.add_argument("--covariance-aware", choices=["spectral", "frobenius"], default=None,
+    ap.add_argument("--covariance-aware", choices=["spectral", "frobenius", "frobenius-fast"], default=None,
                     help="add the covariance-aware selection score (pisa_block_heterogeneity) to the step")
     ap.add_argument("--hbar-from-stats", action="store_true",
                     help="covariance-aware selection takes Hbar from the statistics' fp32 hsum (saves one fp64 pass)")
@@ -147,7 +147,8 @@ def main():
     gap = torch.empty(b, h, N, dtype=f32, device=dev)
     out = torch.empty_like(q)
 
-    norm = {None: None, "spectral": pisa.PISA_NORM_SPECTRAL, "frobenius": pisa.PISA_NORM_FROBENIUS}[
+    norm = {None: None, "spectral": pisa.PISA_NORM_SPECTRAL, "frobenius": pisa.PISA_NORM_FROBENIUS,
+            "frobenius-fast": pisa.PISA_NORM_FROBENIUS_FAST}[
         args.covariance_aware]
 
     def step(events=None):
@@ -159,7 +160,8 @@ def main():
         log_m = None
         if norm is not None:       # counted in the select stage
             log_m = pisa.block_heterogeneity(shape, k, v, stats["kbar64"], norm, 1e-6, ws,
-                                             hsum=stats["hsum"] if args.hbar_from_stats else None)
+                                             hsum=stats["hsum"] if (args.hbar_from_stats or
+                                                                    norm == pisa.PISA_NORM_FROBENIUS_FAST) else None)
         pisa.select_into(shape, stats["qbar64"], stats["kbar64"], k_top, idx, gap, ws, log_m)
         if events:
             events[2].record()

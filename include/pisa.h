@@ -45,7 +45,7 @@ enum {
 };
 
 enum { PISA_FP32 = 0, PISA_BF16 = 1 };
-enum { PISA_NORM_SPECTRAL = 0, PISA_NORM_FROBENIUS = 1 };
+enum { PISA_NORM_SPECTRAL = 0, PISA_NORM_FROBENIUS = 1, PISA_NORM_FROBENIUS_FAST = 2 };
 
 typedef struct pisa_shape {
   int32_t batch;      /* >= 1 */
@@ -104,6 +104,11 @@ int32_t pisa_block_stats(const pisa_shape* shape, const void* q, const void* k, 
  *              below 1e-7 theta (at most 300 steps), M_j = sqrt(theta): within 5e-8 relative of a
  *              singular value by construction, in practice equal to the largest one to rounding;
  *              PISA_NORM_FROBENIUS: exact (fp64), cheaper, an upper bound of the spectral norm.
+ *              PISA_NORM_FROBENIUS_FAST (bf16 inputs only, needs hsum): the Frobenius norm with H_j
+ *              rebuilt the way pisa_block_stats builds it (bf16 matrix cores, K centred and split
+ *              hi + lo, fp32 accumulation: the very bits that were summed into hsum) instead of
+ *              in fp64: one pass at the cost of the statistics pass; M_j within 1e-6 of the
+ *              largest M_j of the head (1e-7 measured).  kbar64 and workspace are not used and may be NULL.
  *   kbar64     fp64 [batch,heads,N,d] as written by pisa_block_stats
  *   hsum       NULL: Hbar is accumulated here in fp64 (one more pass over K and V), and M_j matches
  *              a plain fp64 evaluation to rounding.  Or fp32 [batch,heads,d,d] as written by
@@ -111,7 +116,7 @@ int32_t pisa_block_stats(const pisa_shape* shape, const void* q, const void* k, 
  *              carries the fp32 rounding of hsum (about 1e-6 of its largest entry), and M_j an
  *              error of about 1e-7 relative, since ||Hbar|| is a fraction of ||H_j - Hbar||.
  *   log_m      fp64 [batch,heads,N], written
- * All arithmetic is fp64.  `workspace` must hold pisa_workspace_bytes(shape).
+ * All arithmetic is fp64 except in the FAST kind.  `workspace` must hold pisa_workspace_bytes(shape).
  * The paper enables this score for image models only; pass log_m as `col_bias` to pisa_select.
  */
 int32_t pisa_block_heterogeneity(const pisa_shape* shape, const void* k, const void* v,

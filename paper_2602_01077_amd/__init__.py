@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_PKG_DIR, "libpisa.so")
 
 PISA_OK, PISA_INVALID_ARG, PISA_UNSUPPORTED, PISA_WORKSPACE_TOO_SMALL, PISA_HIP_ERROR = range(5)
 PISA_FP32, PISA_BF16 = 0, 1
-PISA_NORM_SPECTRAL, PISA_NORM_FROBENIUS = 0, 1
+PISA_NORM_SPECTRAL, PISA_NORM_FROBENIUS, PISA_NORM_FROBENIUS_FAST = 0, 1, 2
 
 EXPORTS = ("pisa_num_blocks", "pisa_topk_count", "pisa_workspace_bytes", "pisa_block_stats",
            "pisa_block_heterogeneity", "pisa_select", "pisa_attention", "pisa_attention_static",
@@ -184,7 +184,8 @@ def block_heterogeneity(shape: PisaShape, k, v, kbar64, norm: int = PISA_NORM_SP
                         ) -> torch.Tensor:
     """pisa_block_heterogeneity.  Returns log(M_j + eps), fp64 [b,h,N].  hsum (fp32, from
     block_stats) lets the library take Hbar from it instead of accumulating it again in fp64."""
-    b, h, n, _ = kbar64.shape
+    b, h = k.shape[0], k.shape[1]
+    n = num_blocks(shape.seq_len, shape.block)
     log_m = torch.empty(b, h, n, dtype=torch.float64, device=k.device)
     ws = alloc_workspace(shape, k.device) if workspace is None else workspace
     _check(_lib.pisa_block_heterogeneity(
@@ -324,7 +325,8 @@ def forward_in_steps(q, k, v, block: int = 64, sparsity: float = 0.85, first_ord
     ws = alloc_workspace(shape, q.device)
     stats = block_stats(q, k, v, block, ws)
     log_m = block_heterogeneity(shape, k, v, stats["kbar64"], norm, eps, ws,
-                                hsum=stats["hsum"] if hbar_from_stats else None) if covariance_aware else None
+                                hsum=stats["hsum"] if (hbar_from_stats or norm == PISA_NORM_FROBENIUS_FAST) else None
+                                ) if covariance_aware else None
     idx, gap = select(shape, stats["qbar64"], stats["kbar64"], k_top, ws, col_bias=log_m)
     out, lse = attention(shape, q, k, v, stats["kbar"] if approximate else None,
                          stats["vsum"] if approximate else None,

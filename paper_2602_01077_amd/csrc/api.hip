@@ -142,11 +142,21 @@ int32_t pisa_block_heterogeneity(const pisa_shape* shape, const void* k, const v
   Dims dm;
   int32_t rc = resolve(shape, &dm);
   if (rc != PISA_OK) return rc;
-  if (!k || !v || !kbar64 || !log_m) return fail(PISA_INVALID_ARG, "k, v, kbar64, log_m must not be NULL");
-  if (norm_kind != PISA_NORM_SPECTRAL && norm_kind != PISA_NORM_FROBENIUS)
-    return fail(PISA_INVALID_ARG, "norm_kind must be PISA_NORM_SPECTRAL (0) or PISA_NORM_FROBENIUS (1)");
+  if (norm_kind != PISA_NORM_SPECTRAL && norm_kind != PISA_NORM_FROBENIUS && norm_kind != PISA_NORM_FROBENIUS_FAST)
+    return fail(PISA_INVALID_ARG, "norm_kind must be PISA_NORM_SPECTRAL (0), PISA_NORM_FROBENIUS (1) or "
+                                  "PISA_NORM_FROBENIUS_FAST (2)");
   if (!(eps >= 0.0)) return fail(PISA_INVALID_ARG, "eps must be >= 0");
   PISA_CHECK_ALIGN(k, v, kbar64, hsum, log_m, workspace);
+  if (norm_kind == PISA_NORM_FROBENIUS_FAST) {
+    if (!k || !v || !log_m) return fail(PISA_INVALID_ARG, "k, v, log_m must not be NULL");
+    if (dm.dtype != PISA_BF16)
+      return fail(PISA_UNSUPPORTED, "PISA_NORM_FROBENIUS_FAST runs on the bf16 matrix cores: bf16 inputs only");
+    if (!hsum) return fail(PISA_INVALID_ARG, "PISA_NORM_FROBENIUS_FAST needs hsum (as written by pisa_block_stats)");
+    hipError_t e = launch_block_heterogeneity_fast(dm, k, v, hsum, eps, log_m, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail("pisa_block_heterogeneity", e);
+    return PISA_OK;
+  }
+  if (!k || !v || !kbar64 || !log_m) return fail(PISA_INVALID_ARG, "k, v, kbar64, log_m must not be NULL");
   size_t need = hetero_workspace_bytes(dm);
   if (!workspace) return fail(PISA_INVALID_ARG, "workspace is NULL (need %zu bytes)", need);
   if (workspace_bytes < need)

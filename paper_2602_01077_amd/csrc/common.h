@@ -73,6 +73,9 @@ hipError_t launch_block_heterogeneity(const Dims& dm, const void* k, const void*
                                       const float* hsum, int spectral, int n_iter, double eps, double* log_m,
                                       double* workspace, hipStream_t stream);
 
+hipError_t launch_block_heterogeneity_fast(const Dims& dm, const void* k, const void* v, const float* hsum,
+                                           double eps, double* log_m, hipStream_t stream);
+
 // Arguments of the attention kernels (dense and PISA share them).
 struct AttnArgs {
   const void* q;

@@ -73,13 +73,19 @@ __device__ inline bf16x8 read_operand(LDS_PTR(const unsigned char) tile, int lan
 // Head_dim 64: a 256-byte wave-load is two rows (lane = row parity x channel pair), a lane
 // holds 8 rows per tensor instead of 16, the two row parities are added with one lane
 // exchange, and the 64 x 64 matrix H is four 32 x 32 tiles, one per wave.
-template <int D, int TPB>
+//
+// HETERO: the same walk used for the covariance-aware score instead of the statistics: every
+// block's H_j is rebuilt exactly as above (same centring, same hi/lo split, same products, so
+// the same bits that went into hsum), kept per block instead of summed over the chunk, and
+// reduced to log(||H_j - hsum / N||_F + eps); nothing else is written and Q is not read.
+template <int D, int TPB, bool HETERO>
 __global__ __launch_bounds__(256, 2) void stats_bf16_kernel(
     const unsigned int* __restrict__ q, const unsigned int* __restrict__ k, const unsigned int* __restrict__ v,
     float* __restrict__ qbar, float* __restrict__ kbar, float* __restrict__ vsum,
     double* __restrict__ qbar64, double* __restrict__ kbar64, float* __restrict__ partial_h,
     unsigned short* __restrict__ kcen, unsigned short* __restrict__ vbar, int npad,
-    int L, int N, int chunk_blocks, int n_chunks) {
+    int L, int N, int chunk_blocks, int n_chunks,
+    const float* __restrict__ hsum, double eps, double* __restrict__ log_m) {
   constexpr int B = TPB * kTile;
   constexpr int TILEB = kTile * 2 * D;
   constexpr int LPR = D / 2;            // lanes per row (one channel pair each)
@@ -95,6 +101,7 @@ __global__ __launch_bounds__(256, 2) void stats_bf16_kernel(
   __shared__ float vsub[2][D];          // sub-block value sums Vhat_s
   __shared__ float dks[2][D];           // c_s - kbar_j
   __shared__ float kmean_s[D];
+  __shared__ double hnorm_s[4];         // HETERO: per-wave sums of squares
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: row addresses stay scalar
@@ -115,6 +122,10 @@ __global__ __launch_bounds__(256, 2) void stats_bf16_kernel(
   f32x16 acc[NB];
 #pragma unroll
   for (int bt = 0; bt < NB; ++bt) acc[bt] = (f32x16){0};
+
+  // HETERO: 1 / N, and this head's hsum (read per block from L2: 64 more registers would not fit)
+  const float inv_n = 1.f / (float)N;
+  const float* hs_head = HETERO ? hsum + bh * (size_t)D * D : nullptr;
 
   // Optional second form of the block outputs, for the attention kernel's centroid phase: the
   // key mean and the value mean of block j as bf16 rows of tiles [bh][npad][D] (the fp32
@@ -150,7 +161,7 @@ __global__ __launch_bounds__(256, 2) void stats_bf16_kernel(
   unsigned int kx[NR] = {}, vx[NR] = {}, qx[NR] = {}, kn[NR] = {}, vn[NR] = {};
   if (j_begin < j_end) {
     const int rows = min(kTile, L - j_begin * B);
-    load_rows(qh, j_begin * B, rows, qx);
+    if (!HETERO) load_rows(qh, j_begin * B, rows, qx);
     load_rows(kh, j_begin * B, rows, kx);
     load_rows(vh, j_begin * B, rows, vx);
   }
@@ -198,7 +209,7 @@ __global__ __launch_bounds__(256, 2) void stats_bf16_kernel(
         *reinterpret_cast<f64x2*>(&red[1][wave][2 * cp]) = (f64x2){sk0, sk1};
         *reinterpret_cast<f64x2*>(&red[2][wave][2 * cp]) = (f64x2){sv0, sv1};
       }
-      load_rows(qh, next_row0, next_rows, qx);    // Q(t) is used up
+      if (!HETERO) load_rows(qh, next_row0, next_rows, qx);    // Q(t) is used up
       __syncthreads();
       if (tid < D) {
         const double sq = ((red[0][0][tid] + red[0][1][tid]) + red[0][2][tid]) + red[0][3][tid];
@@ -206,14 +217,16 @@ __global__ __launch_bounds__(256, 2) void stats_bf16_kernel(
         const double sv = ((red[2][0][tid] + red[2][1][tid]) + red[2][2][tid]) + red[2][3][tid];
         const double cm = sk / (double)rows;
         if (TPB == 1) {
-          const double qm = sq / (double)rows;
-          const size_t o = (bh * N + j) * D + tid;
-          qbar[o] = (float)qm;
-          kbar[o] = (float)cm;
-          vsum[o] = (float)sv;
-          if (qbar64) qbar64[o] = qm;
-          if (kbar64) kbar64[o] = cm;
-          centroid_rows(j, (float)cm, (float)sv, rows);
+          if (!HETERO) {
+            const double qm = sq / (double)rows;
+            const size_t o = (bh * N + j) * D + tid;
+            qbar[o] = (float)qm;
+            kbar[o] = (float)cm;
+            vsum[o] = (float)sv;
+            if (qbar64) qbar64[o] = qm;
+            if (kbar64) kbar64[o] = cm;
+            centroid_rows(j, (float)cm, (float)sv, rows);
+          }
         } else {
           tot[0][tid] = sub == 0 ? sq : tot[0][tid] + sq;
           tot[1][tid] = sub == 0 ? sk : tot[1][tid] + sk;
@@ -267,13 +280,15 @@ __global__ __launch_bounds__(256, 2) void stats_bf16_kernel(
       // ---- block outputs from the sub-block totals, then the rank-one corrections ----
       if (tid < D) {
         const double qm = tot[0][tid] / (double)block_rows, km = tot[1][tid] / (double)block_rows;
-        const size_t o = (bh * N + j) * D + tid;
-        qbar[o] = (float)qm;
-        kbar[o] = (float)km;
-        vsum[o] = (float)tot[2][tid];
-        if (qbar64) qbar64[o] = qm;
-        if (kbar64) kbar64[o] = km;
-        centroid_rows(j, (float)km, (float)tot[2][tid], block_rows);
+        if (!HETERO) {
+          const size_t o = (bh * N + j) * D + tid;
+          qbar[o] = (float)qm;
+          kbar[o] = (float)km;
+          vsum[o] = (float)tot[2][tid];
+          if (qbar64) qbar64[o] = qm;
+          if (kbar64) kbar64[o] = km;
+          centroid_rows(j, (float)km, (float)tot[2][tid], block_rows);
+        }
         for (int sub = 0; sub < n_sub; ++sub) dks[sub][tid] = (float)(csub[sub][tid] - km);
       }
       __syncthreads();
@@ -288,7 +303,34 @@ __global__ __launch_bounds__(256, 2) void stats_bf16_kernel(
       }
       __syncthreads();                            // dks / vsub / tot are rewritten by the next block
     }
+    if (HETERO) {
+      // acc holds H_j; this lane's elements sit at fixed positions of the matrix
+      double ss = 0.0;
+      const float* hp = hs_head;
+      asm volatile("" : "+s"(hp));    // keeps the 64 loads below inside the block loop (hoisted, they spill)
+#pragma unroll
+      for (int bt = 0; bt < NB; ++bt) {
+        float hb[16];                 // the elements of hsum at this lane's accumulator positions (see the store below)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          hb[r] = hp[(size_t)(32 * ktile + (r / 4) * 8 + 4 * h + (r % 4)) * D + 32 * (vtile0 + bt) + lam];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const double dlt = (double)fmaf(-hb[r], inv_n, acc[bt][r]);   // both terms carry fp32 rounding already
+          ss = fma(dlt, dlt, ss);
+          acc[bt][r] = 0.f;
+        }
+      }
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+      if (lane == 0) hnorm_s[wave] = ss;
+      __syncthreads();
+      if (tid == 0)
+        log_m[bh * N + j] = log(sqrt(((hnorm_s[0] + hnorm_s[1]) + hnorm_s[2]) + hnorm_s[3]) + eps);
+      // hnorm_s is written again only after the next block's barriers
+    }
   }
+  if (HETERO) return;
   // acc[bt][r] = H[32 ktile + (r/4)*8 + 4h + r%4][32 (vtile0 + bt) + lam]
   float* ph = partial_h + (bh * n_chunks + chunk) * (size_t)D * D;
 #pragma unroll
@@ -307,15 +349,34 @@ hipError_t launch_block_stats_bf16(const Dims& dm, const void* q, const void* k,
   const int npad = ((dm.N + kTile - 1) / kTile) * kTile;
   const dim3 grid(plan.n_chunks, dm.bh());
 #define PISA_STATS_BF16(DD, TPB)                                                                           \
-  hipLaunchKernelGGL((stats_bf16_kernel<DD, TPB>), grid, dim3(256), 0, stream, (const unsigned int*)q,     \
+  hipLaunchKernelGGL((stats_bf16_kernel<DD, TPB, false>), grid, dim3(256), 0, stream, (const unsigned int*)q, \
                      (const unsigned int*)k, (const unsigned int*)v, qbar, kbar, vsum, qbar64, kbar64,     \
                      partial_h, (unsigned short*)kcen, (unsigned short*)vbar, npad, dm.L, dm.N,                \
-                     plan.chunk_blocks, plan.n_chunks)
+                     plan.chunk_blocks, plan.n_chunks, nullptr, 0.0, nullptr)
   if (dm.d == 128 && dm.B == kTile) PISA_STATS_BF16(128, 1);
   else if (dm.d == 128) PISA_STATS_BF16(128, 2);
   else if (dm.B == kTile) PISA_STATS_BF16(64, 1);
   else PISA_STATS_BF16(64, 2);
 #undef PISA_STATS_BF16
+  return hipGetLastError();
+}
+
+// log(||H_j - hsum / N||_F + eps) per block with H_j rebuilt on the bf16 matrix cores (fp32-level
+// accuracy, the accuracy hsum itself has).
+hipError_t launch_block_heterogeneity_fast(const Dims& dm, const void* k, const void* v, const float* hsum,
+                                           double eps, double* log_m, hipStream_t stream) {
+  const StatsPlan plan = stats_plan(dm);
+  const dim3 grid(plan.n_chunks, dm.bh());
+#define PISA_HET_FAST(DD, TPB)                                                                              \
+  hipLaunchKernelGGL((stats_bf16_kernel<DD, TPB, true>), grid, dim3(256), 0, stream, nullptr,               \
+                     (const unsigned int*)k, (const unsigned int*)v, nullptr, nullptr, nullptr, nullptr,    \
+                     nullptr, nullptr, nullptr, nullptr, 0, dm.L, dm.N, plan.chunk_blocks, plan.n_chunks,   \
+                     hsum, eps, log_m)
+  if (dm.d == 128 && dm.B == kTile) PISA_HET_FAST(128, 1);
+  else if (dm.d == 128) PISA_HET_FAST(128, 2);
+  else if (dm.B == kTile) PISA_HET_FAST(64, 1);
+  else PISA_HET_FAST(64, 2);
+#undef PISA_HET_FAST
   return hipGetLastError();
 }
 

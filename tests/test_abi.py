@@ -79,6 +79,17 @@ def test_bad_shapes_are_rejected(kw, code):
                                 FAKE, 1 << 40, None) == code
 
 
+def test_fast_frobenius_kind_is_validated():
+    lib = pisa.raw()
+    bf = shape(dtype=pisa.PISA_BF16, head_dim=128)
+    call = lambda s, hsum, kind: lib.pisa_block_heterogeneity(ctypes.byref(s), FAKE, FAKE, None, hsum, kind, 1e-6,
+                                                              FAKE, None, 0, None)
+    assert call(shape(), FAKE, pisa.PISA_NORM_FROBENIUS_FAST) == pisa.PISA_UNSUPPORTED      # fp32 inputs
+    assert call(bf, None, pisa.PISA_NORM_FROBENIUS_FAST) == pisa.PISA_INVALID_ARG           # needs hsum
+    assert call(bf, FAKE, 3) == pisa.PISA_INVALID_ARG
+    assert call(bf, FAKE, pisa.PISA_NORM_FROBENIUS) == pisa.PISA_INVALID_ARG                # the fp64 kinds need kbar64
+
+
 def test_forward_validation():
     lib = pisa.raw()
     s = shape(dtype=pisa.PISA_BF16, head_dim=128)
