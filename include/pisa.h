@@ -4,10 +4,10 @@
  * C ABI.  Every entry point below follows one step of the paper's forward-pass
  * algorithm (Methodology, "Hardware-aware Kernel Implementation", Alg. 1):
  *
- *   pisa_block_stats   Alg. 1 line 1   ("Prepare": block means, block value sums, global H)
- *   pisa_select        Alg. 1 line 2   (block-wise top-k of pooled scores)
+ *   pisa_block_stats   Alg. 1, "Prepare" step   ("Prepare": block means, block value sums, global H)
+ *   pisa_select        Alg. 1, "Select" step   (block-wise top-k of pooled scores)
  *   pisa_block_heterogeneity           ("Covariance-Aware Block Selection": log(M_j + eps))
- *   pisa_attention     Alg. 1 lines 4-23 (Phase 1 exact, Phase 2 zeroth-order scan,
+ *   pisa_attention     Alg. 1, the loop over query blocks (its three phases) (Phase 1 exact, Phase 2 zeroth-order scan,
  *                                       Phase 3 global first-order term, one online softmax)
  *   dense_attention    Preliminaries, first equation (softmax(QK^T/sqrt d)V), the
  *                      speed-up baseline, written with the same tile loop
@@ -76,7 +76,7 @@ int32_t pisa_topk_count(int32_t num_blocks, double sparsity);
 size_t pisa_workspace_bytes(const pisa_shape* shape);
 
 /*
- * Alg. 1 line 1.  For every (batch, head):
+ * Alg. 1, "Prepare" step.  For every (batch, head):
  *   qbar[i,:]  = mean of the rows of query block i            fp32 [batch,heads,N,d]
  *   kbar[j,:]  = mean of the rows of key block j  (centroid)  fp32 [batch,heads,N,d]
  *   vsum[j,:]  = sum  of the rows of value block j            fp32 [batch,heads,N,d]
@@ -125,7 +125,7 @@ int32_t pisa_block_heterogeneity(const pisa_shape* shape, const void* k, const v
                                  void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * Alg. 1 line 2.  For every (batch, head, query block i): logits z_ij = s * qbar_i . kbar_j
+ * Alg. 1, "Select" step.  For every (batch, head, query block i): logits z_ij = s * qbar_i . kbar_j
  * (+ col_bias[j] if given: the selection-score equation with or without its covariance term;
  * softmax is monotone so the logits are ranked directly), and the k_top largest are kept;
  * equal logits go to the lower block index.
@@ -142,12 +142,12 @@ int32_t pisa_select(const pisa_shape* shape, const double* qbar64, const double*
                     void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * Alg. 1 lines 4-23 for every (batch, head, query block i), rows t of the block:
+ * Alg. 1, the loop over query blocks (its three phases) for every (batch, head, query block i), rows t of the block:
  *   D_t = sum_{j in S_i} sum_n exp(s q_t k_{j,n}^T)  +  sum_{j in U_i} B_j exp(s q_t kbar_j^T)
  *   N_t = sum_{j in S_i} sum_n exp(s q_t k_{j,n}^T) v_{j,n}
  *       + sum_{j in U_i} exp(s q_t kbar_j^T) vsum_j
  *       + (T_t / L) (s q_t) hsum ,   T_t = sum_{j in U_i} B_j exp(s q_t kbar_j^T)
- *   out_t = N_t / D_t                         (hybrid equations; Alg. 1 lines 22-23)
+ *   out_t = N_t / D_t                         (hybrid equations; the last step of Alg. 1)
  * with S_i = idx[i, :], U_i its complement, all inside one running-max softmax.
  *   kbar, vsum, hsum: as written by pisa_block_stats.  hsum == NULL drops the first-order
  *            term (the zeroth-order variant of the ablation study).  kbar == vsum == NULL

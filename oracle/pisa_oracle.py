@@ -14,10 +14,10 @@ query block `i` attends exactly, `U_i` its complement, `s` the softmax scale.
 
 What is computed (citations are to the paper):
 
-* `block_stats`  -- "Prepare" step of the forward-pass algorithm (Alg. 1,
-  line 1) with the definitions of the block centroid and of `H_j` from the
+* `block_stats`  -- "Prepare" step of the forward-pass algorithm (Alg. 1)
+  with the definitions of the block centroid and of `H_j` from the
   "Formulation" / "Global First-Order Correction" paragraphs.
-* `select`       -- block-wise top-k of pooled scores (Alg. 1 line 2; the score
+* `select`       -- block-wise top-k of pooled scores (Alg. 1, "Select" step; the score
   is the covariance-aware score equation; its `log(M_j + eps)` term, which the
   paper switches on for image models only, enters as an optional column bias
   built from `block_heterogeneity`).
@@ -81,7 +81,7 @@ def _f64(x) -> np.ndarray:
 
 
 # ----------------------------------------------------------------------------
-# Prepare: block statistics  (Alg. 1 line 1)
+# Prepare: block statistics  (Alg. 1, "Prepare" step)
 # ----------------------------------------------------------------------------
 def block_stats(Q, K, V, B: int, per_block_H: bool = False):
     """Return dict(qbar[N,d], kbar[N,d], vsum[N,d], hsum[d,d], (Hj[N,d,d])).
@@ -115,7 +115,7 @@ def block_stats(Q, K, V, B: int, per_block_H: bool = False):
 
 
 # ----------------------------------------------------------------------------
-# Select: pooled block scores and top-k  (Alg. 1 line 2)
+# Select: pooled block scores and top-k  (Alg. 1, "Select" step)
 # ----------------------------------------------------------------------------
 def pooled_logits(qbar, kbar, scale: float) -> np.ndarray:
     return scale * (_f64(qbar) @ _f64(kbar).T)
@@ -243,7 +243,7 @@ def attention_head(Q, K, V, B: int, idx: Optional[np.ndarray], scale: float,
 
 
 # ----------------------------------------------------------------------------
-# The same result the way the forward-pass algorithm states it  (Alg. 1 lines 4-23)
+# The same result the way the forward-pass algorithm states it  (Alg. 1, the loop over query blocks (its three phases))
 # ----------------------------------------------------------------------------
 def alg1_forward(Q, K, V, B: int, C: int, idx: np.ndarray, scale: float,
                  stats: Optional[dict] = None, blocks: Optional[Sequence[int]] = None):

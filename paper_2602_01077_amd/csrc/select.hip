@@ -1,4 +1,4 @@
-// pisa_select: pooled block logits and top-k per query block (Alg. 1 line 2), with the
+// pisa_select: pooled block logits and top-k per query block (Alg. 1, "Select" step), with the
 // optional log(M_j + eps) column bias of the covariance-aware score.
 //
 // Two kernels (one fused kernel when N <= 128).  (1) fp64 logits z[bh][i][j] = s * qbar_i . kbar_j on the fp64 matrix

@@ -1,6 +1,6 @@
 // pisa_block_stats: block means of Q and K, block sums of V, and the global
 // first-order statistic  hsum = sum_j sum_n (k_{j,n} - kbar_j)^T v_{j,n}
-// (Alg. 1 line 1; H_j as defined in the "Global First-Order Correction" paragraph).
+// (Alg. 1, "Prepare" step; H_j as defined in the "Global First-Order Correction" paragraph).
 //
 // Grid: (n_chunks, batch*heads).  A workgroup walks `chunk_blocks` consecutive
 // blocks of one head, keeps its share of H in registers, and writes one partial

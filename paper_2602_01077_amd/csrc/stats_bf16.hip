@@ -1,5 +1,5 @@
 // pisa_block_stats for bf16 inputs, head_dim 128 or 64, block 64 or 128: one streaming pass
-// (Alg. 1 line 1).  Written out for head_dim 128; the differences at 64 are noted where they occur.
+// (Alg. 1, "Prepare" step).  Written out for head_dim 128; the differences at 64 are noted where they occur.
 //
 // Grid (n_chunks, batch*heads); a workgroup of 4 waves walks `chunk_blocks` consecutive
 // blocks of one head.  Per 64-token (sub-)block:
