@@ -726,6 +726,18 @@ def test_forward_in_one_call_equals_the_three_calls(lib, dtype, d, B, L, heads, 
         assert torch.equal(lse, ref["lse"])
 
 
+def test_forward_in_one_call_batch_of_two(lib):
+    """batch > 1 through the one-call entry point (the workspace regions are laid out per (batch, head))."""
+    w = WORKLOADS["tiny"].with_(name="one-call-b2", heads=3, seq_len=1100, head_dim=128, dtype="bf16", sparsity=0.8,
+                                seed=73)
+    parts = [make_qkv(w, batch_index=b) for b in range(2)]
+    q, k, v = (torch.cat([p[i] for p in parts], dim=0).contiguous().to(DEV) for i in range(3))
+    ref = lib.forward_in_steps(q, k, v, w.block, w.sparsity, want_lse=True)
+    out, lse = lib.forward(lib.make_shape(q, w.block), q, k, v, ref["k_top"], want_lse=True)
+    torch.cuda.synchronize()
+    assert torch.equal(out, ref["out"]) and torch.equal(lse, ref["lse"])
+
+
 def test_forward_in_one_call_against_the_oracle(lib):
     """The one-call entry point compared with the oracle directly (FLUX-sized heads, bf16)."""
     w = WORKLOADS["flux"].with_(name="one-call-oracle", heads=2, seed=72)
