@@ -366,6 +366,45 @@ def test_three_calls_replay_from_a_hip_graph(lib):
         assert torch.equal(out, want_out), rep
 
 
+def test_one_call_replays_from_a_hip_graph(lib):
+    """The same for pisa_forward (three launches, everything in one workspace)."""
+    w = WORKLOADS["flux"].with_(heads=4, seq_len=3000, grid=None)
+    q, k, v = (x.to(DEV) for x in make_qkv(w))
+    shape = lib.make_shape(q, w.block)
+    k_top = wl_topk(w)
+    ws = torch.empty(lib.forward_workspace_bytes(shape, k_top), dtype=torch.uint8, device=DEV)
+    out = torch.empty_like(q)
+    lse = torch.empty(q.shape[:3], dtype=torch.float32, device=DEV)
+
+    def run():
+        lib.forward(shape, q, k, v, k_top, out=out, lse=lse, workspace=ws)
+
+    run()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            run()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        q.mul_(1.0 + 0.25 * rep)                        # new inputs, same buffers
+        v.add_(0.125 * rep)
+        run()
+        torch.cuda.synchronize()
+        want_out, want_lse = out.clone(), lse.clone()
+        out.zero_()
+        lse.zero_()
+        ws.fill_(0xFF)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, want_out), rep
+        assert torch.equal(lse, want_lse), rep
+
+
 @pytest.mark.parametrize("dtype,d,scale", [("bf16", 128, 0.2), ("fp32", 64, 0.05), ("bf16", 128, 0.01)])
 def test_custom_softmax_scale(lib, dtype, d, scale):
     """pisa_shape.scale other than 1/sqrt(d) must reach the selection logits, both softmax
