@@ -173,52 +173,67 @@ template <int D> struct State {
 };
 
 // Per-lane constants of the staging layout, computed once per kernel.
-// LDS-DMA: wave w fills KB numbers w, w+4, ... of a staged tile (four per wave at D = 128, two
-// at D = 64); a KB is RPL rows, so load i covers tile rows r0 + 4 RPL i with r0 = RPL w +
-// lane / CPR.  Rows that far apart share their swizzle, so one per-lane byte offset per format
-// serves all loads (the +4096 i goes into the scalar base).
+// LDS-DMA: a staged tile is kTile * ROWB / 1024 pieces of 1 KB (RPL rows each); wave w fills
+// the NLD consecutive pieces NLD w .. NLD w + NLD - 1, i.e. tile rows 16 w .. 16 w + 15, with
+// NLD instructions that differ only in their immediate offset (i KB), which the hardware adds
+// to the global address and to the LDS address alike: one scalar base and one M0 value serve
+// all of a wave's loads of a tile.  The bank swizzle depends on the row, so each load has its
+// own per-lane byte offset (position inside its 1 KB piece).
 struct LaneCtx {
-  unsigned dma_k, dma_v;   // byte offset inside a global tile: K format / V format
-  int dma_r0;              // tile row of the first load
+  unsigned dma_k[4], dma_v[4];   // per-lane byte offset inside piece i of a global tile: K format / V format
+  int dma_r0;              // tile row of the first load (load i: row dma_r0 + RPL i)
   unsigned wave;           // wave index (uniform)
   LDS_PTR(const unsigned char) kbase;   // K operand address of contraction step 0
   LDS_PTR(const unsigned char) vbase;   // V^T operand address of channel tile 0
   int h;
 };
 
-// Asynchronous global -> LDS load of one 64-row tile (256-byte rows) starting at `tile_base`
-// (wave-uniform).  The LDS-DMA instruction goes through inline asm on purpose: the compiler
-// then does not track it and puts no vmcnt wait in front of LDS reads of the other stage;
-// completion is enforced by wait_async_loads() + barrier before a stage is read.
+// One LDS-DMA instruction: 64 lanes x 16 bytes, global (base + voff + IMM) -> LDS (M0 + IMM +
+// 16 lane).  It goes through inline asm on purpose: the compiler then does not track it and
+// puts no vmcnt wait in front of LDS reads of the other stage; completion is enforced by
+// wait_async_loads() + barrier before a stage is read.  M0 is written by the caller.
+template <int IMM>
+__device__ inline void dma_1kb(unsigned voff, const unsigned char* base /* wave-uniform */) {
+  static_assert(IMM >= 0 && IMM < 4096, "13-bit signed immediate offset");
+  asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" : : "v"(voff), "s"(base), "n"(IMM) : "memory");
+}
 // The instruction takes its LDS base from M0; a scalar write of M0 needs one wait state before
 // an LDS-DMA instruction reads it, and the compiler cannot see inside the asm string, so the
 // s_nop is written out.
-// rows_avail < 64: rows past the end are replaced by the last valid row (finite data; such
-// keys are masked by the caller).
+__device__ inline void set_dma_lds_base(unsigned lds_byte_address /* wave-uniform */) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0" : : "s"(lds_byte_address) : "memory", "m0");
+}
+
+// Asynchronous global -> LDS load of one 64-row tile starting at `tile_base` (wave-uniform):
+// this wave's NLD pieces.  rows_avail < 64: rows past the end are replaced by the last valid
+// row (finite data; such keys are masked by the caller).
 template <int D, bool KFMT>
 __device__ inline void load_tile_async(const LaneCtx& lc, const unsigned char* tile_base, int rows_avail,
                                        unsigned lds_stage /* LDS byte address of the destination tile */) {
-  const unsigned voff = KFMT ? lc.dma_k : lc.dma_v;
-  const unsigned m0_0 = __builtin_amdgcn_readfirstlane(lds_stage + lc.wave * 1024);
   constexpr int NLD = Geo<D>::NLD, RPL = Geo<D>::RPL, ROWB = Geo<D>::ROWB;
+  const unsigned piece0 = __builtin_amdgcn_readfirstlane(lc.wave * (NLD * 1024));
+  set_dma_lds_base(lds_stage + piece0);
   if (rows_avail >= kTile) {
-#pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                   :
-                   : "s"(m0_0 + i * 4096), "v"(voff), "s"(tile_base + i * 4096)
-                   : "memory", "m0");
+    const unsigned char* base = tile_base + piece0;
+    dma_1kb<0>(KFMT ? lc.dma_k[0] : lc.dma_v[0], base);
+    dma_1kb<1024>(KFMT ? lc.dma_k[1] : lc.dma_v[1], base);
+    if (NLD == 4) {
+      dma_1kb<2048>(KFMT ? lc.dma_k[2] : lc.dma_v[2], base);
+      dma_1kb<3072>(KFMT ? lc.dma_k[3] : lc.dma_v[3], base);
     }
   } else {
+    // per-lane source rows, stepped back to the last valid one; the immediate offset still
+    // moves the LDS side, so it is taken off the global address again
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
-      const int r = lc.dma_r0 + 4 * RPL * i;
+      const int r = lc.dma_r0 + RPL * i;
       const int back = max(r - (rows_avail - 1), 0);                    // rows to step back
-      const unsigned char* src = tile_base + i * 4096 + (long long)voff - (long long)back * ROWB;
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                   :
-                   : "s"(m0_0 + i * 4096), "v"(src)
-                   : "memory", "m0");
+      const unsigned voff = KFMT ? lc.dma_k[i] : lc.dma_v[i];
+      const unsigned char* src = tile_base + piece0 + (long long)voff - (long long)back * ROWB;
+      if (i == 0) asm volatile("global_load_lds_dwordx4 %0, off" : : "v"(src) : "memory");
+      if (i == 1) asm volatile("global_load_lds_dwordx4 %0, off offset:1024" : : "v"(src) : "memory");
+      if (i == 2) asm volatile("global_load_lds_dwordx4 %0, off offset:2048" : : "v"(src) : "memory");
+      if (i == 3) asm volatile("global_load_lds_dwordx4 %0, off offset:3072" : : "v"(src) : "memory");
     }
   }
 }
@@ -231,25 +246,21 @@ struct Trip {
   int lo, hi;
 };
 
-// Load i of this wave's share of a stage: the LDS-DMA instruction of load_tile_async, one at a
-// time; the first half of a wave's loads falls into stage rows 0..31 and reads `lo`, the rest `hi`.
-template <int D, bool KFMT>
-__device__ inline void load_stage_part(const LaneCtx& lc, const unsigned char* g, const Trip t,
-                                       unsigned lds_stage, int i) {
-  constexpr int HALF = Geo<D>::NLD / 2;
-  const unsigned voff = KFMT ? lc.dma_k : lc.dma_v;
-  const unsigned m0_0 = __builtin_amdgcn_readfirstlane(lds_stage + lc.wave * 1024);
-  const int off = __builtin_amdgcn_readfirstlane(i < HALF ? t.lo + i * 4096 : t.hi + (i - HALF) * 4096);
-  const unsigned char* src = g + off;
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :
-               : "s"(m0_0 + i * 4096), "v"(voff), "s"(src)
-               : "memory", "m0");
-}
+// This wave's share of a stage: waves 0, 1 fill stage rows 0..31 from `lo`, waves 2, 3 rows
+// 32..63 from `hi`; one source address and one M0 value per wave.
 template <int D, bool KFMT>
 __device__ inline void load_stage(const LaneCtx& lc, const unsigned char* g, const Trip t, unsigned lds_stage) {
-#pragma unroll
-  for (int i = 0; i < Geo<D>::NLD; ++i) load_stage_part<D, KFMT>(lc, g, t, lds_stage, i);
+  constexpr int NLD = Geo<D>::NLD;
+  const unsigned piece0 = __builtin_amdgcn_readfirstlane(lc.wave * (NLD * 1024));
+  const int off = __builtin_amdgcn_readfirstlane((lc.wave < 2 ? t.lo : t.hi) + (int)(lc.wave & 1) * (NLD * 1024));
+  const unsigned char* base = g + off;
+  set_dma_lds_base(lds_stage + piece0);
+  dma_1kb<0>(KFMT ? lc.dma_k[0] : lc.dma_v[0], base);
+  dma_1kb<1024>(KFMT ? lc.dma_k[1] : lc.dma_v[1], base);
+  if (NLD == 4) {
+    dma_1kb<2048>(KFMT ? lc.dma_k[2] : lc.dma_v[2], base);
+    dma_1kb<3072>(KFMT ? lc.dma_k[3] : lc.dma_v[3], base);
+  }
 }
 
 // V-format swizzle: the 32-byte chunk index of row r is XORed with this 3-bit value.  The
@@ -553,11 +564,15 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void attn_bf16_kernel(PB p) {
   lc.h = h;
   lc.wave = __builtin_amdgcn_readfirstlane(wave);
   {
-    const int r = RPL * wave + lane / CPR;       // tile row of this lane's first DMA load
     const int pos = lane % CPR;                  // 16-byte slot inside the LDS row
-    lc.dma_r0 = r;
-    lc.dma_k = r * ROWB + ((pos ^ kswz<D>(r)) << 4);
-    lc.dma_v = r * ROWB + (((((pos >> 1) ^ vswz<D>(r)) << 1) | (pos & 1)) << 4);
+    lc.dma_r0 = RPL * Geo<D>::NLD * wave + lane / CPR;   // tile row of this lane's first DMA load
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int r = lc.dma_r0 + RPL * i;         // tile row of load i; its offset is relative to piece i
+      const int in_piece = (lane / CPR) * ROWB;
+      lc.dma_k[i] = in_piece + ((pos ^ kswz<D>(r)) << 4);
+      lc.dma_v[i] = in_piece + (((((pos >> 1) ^ vswz<D>(r)) << 1) | (pos & 1)) << 4);
+    }
     const int j16 = lane & 15;
     const int kq = 4 * h + (j16 >> 2);           // key offset of this lane's V pointer (= key & 7)
     const int lhalf = (lane >> 4) & 1;
