@@ -2,6 +2,7 @@
 
     python -m paper_2602_01077_amd.study error  [--workload wan] [--heads 8]
     python -m paper_2602_01077_amd.study speed  [--lengths 4096 8192 ...]
+    python -m paper_2602_01077_amd.study l2-miss-cost
 
 `error`  normalised L1 error against the library's dense_attention,
          sum|O - O_dense| / sum|O_dense|, for the keep-or-drop, zeroth-order and hybrid
@@ -10,10 +11,12 @@
 `error --lengths L1 L2 ...`  the same three errors at ONE density over sequence lengths (the
          length axis of that figure): the Wan-style generator on a t x 45 x 80 latent grid cut
          to the length asked for.
+`l2-miss-cost`  pisa_attention at the Wan shape on the real index sets and on lists that make
+         every tile load hit L2, with the shader clock held under each.
 `speed`  ms per call of dense_attention and of the whole PISA path over sequence lengths
          and densities at the paper's kernel-study shape B2-H16-D128 ("Kernel Efficiency
          Evaluation").
-Both print one JSON line per point.
+All print one JSON line per point.
 """
 from __future__ import annotations
 
@@ -144,6 +147,59 @@ def speed_study(args):
             print(json.dumps(row), flush=True)
 
 
+def l2_miss_cost_study(args):
+    """What the L2 misses of the exact phase cost at the Wan shape: pisa_attention on the real index sets
+    against the same trip mix with every workgroup on one pair of rows (the same tiles for everybody, so all
+    tile loads hit L2), each with the shader clock the chip holds meanwhile (the library's clock probe on a
+    second stream).  Under rocprofv3 --pmc the launches come in this order: real x (2 + reps), all-hit x (2 + reps)."""
+    dev = torch.device("cuda:0")
+    w = WORKLOADS["wan"]
+    q, k, v = make_qkv(w, device=dev)
+    shape = pisa.make_shape(q, w.block)
+    ws = pisa.alloc_workspace(shape, dev)
+    st = pisa.block_stats(q, k, v, w.block, ws)
+    n = pisa.num_blocks(w.seq_len, w.block)
+    k_top = pisa.topk_count(n, w.sparsity)
+    idx, _ = pisa.select(shape, st["qbar64"], st["kbar64"], k_top, ws, want_gap=False)
+    # mean overlap of two neighbouring rows of the real index sets -> number of unshared tiles per row
+    a, b = idx[0, :, 0:n - 1:2].long(), idx[0, :, 1:n:2].long()
+    hit = torch.zeros(a.shape[0], a.shape[1], n, dtype=torch.bool, device=dev).scatter_(2, a, True)
+    shared = hit.gather(2, b).float().sum(dim=2).mean().item()
+    pairs = int(round(k_top - shared))
+    g = torch.Generator(device="cpu")
+    g.manual_seed(0)
+    perm = torch.randperm(n - 1, generator=g)
+    row_a = torch.sort(perm[:k_top]).values
+    row_b = torch.sort(torch.cat([perm[pairs:k_top], perm[k_top:k_top + pairs]])).values
+    same = torch.empty(1, w.heads, n, k_top, dtype=torch.int64)
+    same[:, :, 0::2] = row_a
+    same[:, :, 1::2] = row_b
+    same = same.to(dev).to(torch.int32).contiguous()
+    out = torch.empty_like(q)
+    for name, lists in (("real index sets", idx), ("same two rows for every workgroup", same)):
+        run = lambda: pisa.attention(shape, q, k, v, st["kbar"], st["vsum"], st["hsum"], lists, k_top, out=out,
+                                     workspace=ws)
+        run()
+        run()
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        counts = torch.zeros(2, dtype=torch.int64, device=dev)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.reps):
+            run()
+        e1.record()
+        with torch.cuda.stream(side):
+            hz = pisa.probe_shader_clock(8.0, counts)
+        torch.cuda.synchronize()
+        cyc, ticks = (int(x) for x in counts.cpu())
+        ms = e0.elapsed_time(e1) / args.reps
+        ghz = cyc / ticks * hz / 1e9
+        print(json.dumps({"lists": name, "shared_tiles_per_pair_of_rows": round(k_top - pairs if lists is same else shared, 1),
+                          "pisa_attention_ms": round(ms, 3), "shader_clock_GHz": round(ghz, 3),
+                          "ms_x_GHz": round(ms * ghz, 2)}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     sub = ap.add_subparsers(dest="cmd", required=True)
@@ -167,8 +223,10 @@ def main():
     s.add_argument("--sparsity", type=float, nargs="+", default=[0.3, 0.5, 0.7, 0.875])
     s.add_argument("--iters", type=int, default=5)
     s.add_argument("--graph", action="store_true", help="also time the path replayed from a captured HIP graph")
+    m = sub.add_parser("l2-miss-cost")
+    m.add_argument("--reps", type=int, default=6)
     args = ap.parse_args()
-    (error_study if args.cmd == "error" else speed_study)(args)
+    {"error": error_study, "speed": speed_study, "l2-miss-cost": l2_miss_cost_study}[args.cmd](args)
 
 
 if __name__ == "__main__":
