@@ -738,6 +738,8 @@ def test_shader_clock_probe(lib):
     ("bf16", 64, 64, 1300, 3, 0.75),        # head_dim 64
     ("bf16", 64, 128, 2048, 2, 0.5),
     ("bf16", 128, 64, 64 * 200, 2, 0.9),    # N = 200 > 128: selection in two launches, reduction on its own
+    ("bf16", 64, 64, 64 * 150 + 17, 2, 0.8),  # N = 151 > 128, ragged, head_dim 64
+    ("bf16", 128, 128, 128 * 130 + 5, 1, 0.9),  # block 128 with N = 131 > 128
     ("bf16", 128, 64, 640, 2, 1.0),         # k_top = 0: centroids only
     ("bf16", 128, 64, 640, 2, 0.0),         # k_top = N: every block exact
     ("fp32", 64, 64, 1024, 2, 0.75),        # fp32 path: the three stages in a row
