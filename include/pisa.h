@@ -164,6 +164,10 @@ int32_t pisa_select(const pisa_shape* shape, const double* qbar64, const double*
  * k_top == N reproduces dense_attention; k_top == 0 is the pure approximation.
  * N up to 4096 blocks.  `workspace` must hold pisa_workspace_bytes(shape) when k_top < N and
  * kbar is given (it may be NULL otherwise); its contents are overwritten.
+ * bf16, block 64, N >= 256, density k_top / N at most 20 %, workspace given: which two 64-row
+ * query blocks travel in one workgroup is decided from idx (blocks whose rows overlap most are
+ * paired, three small launches ahead of the attention kernel), which changes the order of the
+ * fp32 sums and nothing else; every entry point decides the same way for the same idx.
  */
 int32_t pisa_attention(const pisa_shape* shape, const void* q, const void* k, const void* v,
                        const float* kbar, const float* vsum, const float* hsum,
@@ -174,12 +178,13 @@ int32_t pisa_attention(const pisa_shape* shape, const void* q, const void* k, co
 /*
  * pisa_attention for callers that cannot allocate or carry a workspace: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
- * kernels and the same result bit for bit; the scratch (bf16 centroid tiles, packed hsum)
+ * kernels and the same result bit for bit; the scratch (bf16 centroid tiles, packed hsum,
+ * the tables of the query-block pairing)
  * lives in a device array inside the library of PISA_STATIC_SCRATCH_BYTES, which
  * every GPU the library runs on holds until the process ends.  The call allocates and frees
  * nothing and does not synchronise.
- *   - Shapes whose scratch need (batch * heads * (4 * ceil(N / 64) * 64 * d + 4 * d * d) bytes,
- *     bf16 path) exceeds the array return PISA_WORKSPACE_TOO_SMALL before
+ *   - Shapes whose scratch need (batch * heads * (4 * ceil(N / 64) * 64 * d + 4 * d * d) bytes, plus
+ *     batch * heads * (4 * N * ceil(N / 32) + 32 * N + 8 * ceil(N / 2)) at block 64 with N >= 256; bf16 path) exceeds the array return PISA_WORKSPACE_TOO_SMALL before
  *     any device work; the three bf16 shapes of the paper's models fit.
  *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU
  *     (different streams, or threads) race on it.  Calls on one stream are ordered and safe.
@@ -187,7 +192,7 @@ int32_t pisa_attention(const pisa_shape* shape, const void* q, const void* k, co
  *   - The array's address is looked up on the first call on each device; make that call
  *     outside a stream capture.
  */
-#define PISA_STATIC_SCRATCH_BYTES (32u << 20)
+#define PISA_STATIC_SCRATCH_BYTES (40u << 20)
 int32_t pisa_attention_static(const pisa_shape* shape, const void* q, const void* k, const void* v,
                               const float* kbar, const float* vsum, const float* hsum,
                               const int32_t* idx, int32_t k_top,

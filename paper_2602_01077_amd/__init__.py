@@ -235,7 +235,7 @@ def attention(shape: PisaShape, q, k, v, kbar, vsum, hsum, idx, k_top: int,
     return out, lse
 
 
-STATIC_SCRATCH_BYTES = 32 << 20
+STATIC_SCRATCH_BYTES = 40 << 20
 
 
 def attention_static(shape: PisaShape, q, k, v, kbar, vsum, hsum, idx, k_top: int,

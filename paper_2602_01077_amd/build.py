@@ -17,7 +17,7 @@ UNITS = [("api.hip", "api", []), ("stats.hip", "stats", []), ("stats_bf16.hip", 
          ("select.hip", "select", []), ("hetero.hip", "hetero", []), ("attn_fp32.hip", "attn_fp32", []),
          ("attn_bf16.hip", "attn_bf16_two_tiles", ["-DPISA_ATTN_PART=1"] + ITERATIVE),
          ("attn_bf16.hip", "attn_bf16", ["-DPISA_ATTN_PART=2"]),
-         ("probe.hip", "probe", [])]
+         ("pairing.hip", "pairing", []), ("probe.hip", "probe", [])]
 OBJ_DIR = os.path.join(PKG_DIR, "_build")
 
 

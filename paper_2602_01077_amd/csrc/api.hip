@@ -226,6 +226,8 @@ int32_t pisa_attention(const pisa_shape* shape, const void* q, const void* k, co
     if (need > 0 && !workspace) return fail(PISA_INVALID_ARG, "workspace is NULL (need %zu bytes)", need);
     if (workspace_bytes < need)
       return fail(PISA_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, need %zu", workspace_bytes, need);
+  } else if (workspace && workspace_bytes < attention_workspace_bytes(dm)) {
+    workspace = nullptr;       // not needed in this mode; too small for the optional pairing of query blocks
   }
   AttnArgs a{q, k, v, kbar, vsum, hsum, idx, k_top, out, lse, false, workspace};
   return run_attention(dm, a, stream, "pisa_attention");
@@ -249,16 +251,14 @@ int32_t pisa_attention_static(const pisa_shape* shape, const void* q, const void
   if (dm.N > kMaxBlocks)
     return fail(PISA_UNSUPPORTED, "at most %d blocks are supported (N = %d)", kMaxBlocks, dm.N);
   void* ws = nullptr;
-  if (k_top < dm.N && kbar) {
-    const size_t need = attention_workspace_bytes(dm);
-    if (need > kStaticScratchBytes)
-      return fail(PISA_WORKSPACE_TOO_SMALL,
-                  "this shape needs %zu bytes of scratch, the built-in array holds %zu: use pisa_attention "
-                  "with a caller-owned workspace", need, (size_t)kStaticScratchBytes);
-    if (need > 0) {
-      hipError_t e = static_scratch_ptr(&ws);
-      if (e != hipSuccess) return hip_fail("pisa_attention_static (address of the scratch array)", e);
-    }
+  const size_t need = attention_workspace_bytes(dm);
+  if (k_top < dm.N && kbar && need > kStaticScratchBytes)
+    return fail(PISA_WORKSPACE_TOO_SMALL,
+                "this shape needs %zu bytes of scratch, the built-in array holds %zu: use pisa_attention "
+                "with a caller-owned workspace", need, (size_t)kStaticScratchBytes);
+  if (need > 0 && need <= kStaticScratchBytes) {     // (in the modes that need no scratch it still serves the pairing)
+    hipError_t e = static_scratch_ptr(&ws);
+    if (e != hipSuccess) return hip_fail("pisa_attention_static (address of the scratch array)", e);
   }
   AttnArgs a{q, k, v, kbar, vsum, hsum, idx, k_top, out, lse, false, ws};
   return run_attention(dm, a, stream, "pisa_attention_static");

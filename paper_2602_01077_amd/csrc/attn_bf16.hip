@@ -89,6 +89,7 @@ struct PB {
   int L, B, N, k_top, npad, n_super, total;
   float scale;
   int first_order;
+  const int32_t* pair;    // block 64 only, may be null: [bh][2 * n_super] query blocks of each workgroup (-1: none)
 };
 
 namespace {
@@ -586,6 +587,16 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void attn_bf16_kernel(PB p) {
     lc.vbase = lds + kq * ROWB + 8 * (j16 & 3) + ((lhalf ^ vswz<D>(kq)) << 5);
   }
 
+  // The two query blocks of a block-64 workgroup: neighbours 2 sg, 2 sg + 1, or whatever the
+  // pairing table says (blocks paired by the similarity of their index rows share more tiles).
+  int blk[2] = {tpb == 1 ? 2 * sg : sg, 2 * sg + 1};
+  if (!DENSE && tpb == 1 && p.pair) {
+    blk[0] = p.pair[(bh * p.n_super + sg) * 2];
+    blk[1] = p.pair[(bh * p.n_super + sg) * 2 + 1];
+  }
+  blk[0] = __builtin_amdgcn_readfirstlane(blk[0]);
+  blk[1] = __builtin_amdgcn_readfirstlane(blk[1]);
+
   // The first 256 entries of each block's index row are requested before anything else: they
   // head the chain index row -> trip list -> first tile load, and the Q operand loads queue
   // up behind them.
@@ -594,14 +605,16 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void attn_bf16_kernel(PB p) {
   if (!DENSE) {
 #pragma unroll
     for (int b = 0; b < nqb; ++b) {
-      const int i = tpb == 1 ? 2 * sg + b : sg;
+      const int i = blk[b];
       j_first[b] = -1;
-      if (i < N && tid < p.k_top) j_first[b] = p.idx[(bh * N + i) * (size_t)p.k_top + tid];
+      if (i >= 0 && i < N && tid < p.k_top) j_first[b] = p.idx[(bh * N + i) * (size_t)p.k_top + tid];
     }
   }
 
   // ---- Q^T operand: this lane's query row, D/16 channel slices of 16 ----
-  const int q_row = sg * QROWS + 32 * wave + lam;
+  const int my_blk = (!DENSE && tpb == 1) ? blk[wave >> 1] : -1;
+  const int q_row = (!DENSE && tpb == 1) ? (my_blk < 0 ? L : my_blk * kTile + 32 * (wave & 1) + lam)
+                                         : sg * QROWS + 32 * wave + lam;
   bf16x8 qreg[NKS];
   {
     const __bf16* qg = p.q + bh * (size_t)L * D;
@@ -627,8 +640,8 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void attn_bf16_kernel(PB p) {
     __syncthreads();
 #pragma unroll
     for (int b = 0; b < nqb; ++b) {
-      const int i = tpb == 1 ? 2 * sg + b : sg;
-      if (i < N) {
+      const int i = blk[b];
+      if (i >= 0 && i < N) {
         const int32_t* row = p.idx + (bh * N + i) * (size_t)p.k_top;
         int j = j_first[b];
         for (int t = tid; t < p.k_top; t += 256) {
@@ -1044,7 +1057,7 @@ size_t attention_workspace_bytes(const Dims& dm) {
   if (dm.dtype != PISA_BF16) return 0;
   const size_t npad = (size_t)((dm.N + kTile - 1) / kTile) * kTile;
   const size_t D = dm.d;
-  return (size_t)dm.bh() * (2 * npad * D * 2 + 2 * D * D * 2);
+  return (size_t)dm.bh() * (2 * npad * D * 2 + 2 * D * D * 2) + pairing_workspace_bytes(dm);
 }
 
 void attention_workspace_carve(const Dims& dm, void* workspace, void** kcen, void** vbar, void** hpack) {
@@ -1074,6 +1087,7 @@ static hipError_t launch_attention_bf16_d(const Dims& dm, const AttnArgs& a, hip
   p.total = p.n_super * dm.bh();
   p.scale = dm.scale;
   p.first_order = a.hsum != nullptr;
+
   const int grid = ((p.total + 63) / 64) * 64;
   if (a.dense) return launch_attention_two_tiles<D>(p, true, grid, stream);
   if (a.k_top < dm.N && a.kbar) {
@@ -1091,6 +1105,13 @@ static hipError_t launch_attention_bf16_d(const Dims& dm, const AttnArgs& a, hip
     p.kcen = kcen;
     p.vbar = vbar;
     p.hpack = hpack;
+  }
+  if (pairing_pays(dm, a.k_top) && a.workspace) {
+    // the pairing scratch follows the pre-pass results (whether or not those are in use)
+    unsigned char* after = static_cast<unsigned char*>(a.workspace) +
+                           (size_t)dm.bh() * (2 * (size_t)p.npad * D * 2 + 2 * D * D * 2);
+    hipError_t e = launch_pair_blocks(dm, a.idx, a.k_top, after, &p.pair, stream);
+    if (e != hipSuccess) return e;
   }
   if (dm.B != kTile) return launch_attention_two_tiles<D>(p, false, grid, stream);
   hipLaunchKernelGGL((attn_bf16_kernel<D, false, 1>), dim3(grid), dim3(256), 0, stream, p);

@@ -95,6 +95,12 @@ struct AttnArgs {
 size_t attention_workspace_bytes(const Dims& dm);
 // Where the bf16 attention pre-pass results sit inside a workspace of that size.
 void attention_workspace_carve(const Dims& dm, void* workspace, void** kcen, void** vbar, void** hpack);
+// Pairing of the query blocks that share a block-64 workgroup by the overlap of their index rows
+// (one launch; the table it writes lives in `workspace`, pairing_workspace_bytes large).
+bool pairing_pays(const Dims& dm, int k_top);
+size_t pairing_workspace_bytes(const Dims& dm);
+hipError_t launch_pair_blocks(const Dims& dm, const int32_t* idx, int k_top, void* workspace, const int32_t** pair,
+                              hipStream_t stream);
 // Size of the file-scope device array behind pisa_attention_static, and its address on the
 // current device (resolved on first use, once per device).
 constexpr size_t kStaticScratchBytes = PISA_STATIC_SCRATCH_BYTES;

@@ -806,3 +806,39 @@ def test_forward_rejects_a_small_workspace(lib):
     with pytest.raises(lib.PisaError) as e:
         lib.forward(shape, q, k, v, 4, workspace=ws)
     assert e.value.code == lib.PISA_WORKSPACE_TOO_SMALL
+
+
+@pytest.mark.parametrize("L,approximate", [(64 * 300 - 21, True), (64 * 257, True), (64 * 300 - 21, False)])
+def test_query_blocks_paired_by_row_similarity(lib, L, approximate):
+    """From 256 blocks on, the block-64 kernel pairs the query blocks of a workgroup by the overlap of their index
+    rows instead of taking neighbours.  Whatever the pairing, every row must be written (the output is pre-filled
+    with NaN) and agree with the oracle (sampled blocks: the first, the last, ragged one, and 22 random ones)."""
+    w = WORKLOADS["wan"].with_(name="pairing", heads=2, seq_len=L, grid=None, block_offset_std=0.5, sparsity=0.85,
+                               seed=81)
+    scale = lib.resolved_scale(w.head_dim)
+    q, k, v = make_qkv(w)
+    qd, kd, vd = q.to(DEV), k.to(DEV), v.to(DEV)
+    shape = lib.make_shape(qd, w.block)
+    N, k_top = wl_blocks(w), wl_topk(w)
+    assert N >= 256
+    ws = lib.alloc_workspace(shape, DEV)
+    st = lib.block_stats(qd, kd, vd, w.block, ws)
+    idx, _ = lib.select(shape, st["qbar64"], st["kbar64"], k_top, ws, want_gap=False)
+    out = torch.full_like(qd, float("nan"))
+    lse = torch.full(qd.shape[:3], float("nan"), dtype=torch.float32, device=DEV)
+    lib.attention(shape, qd, kd, vd, st["kbar"] if approximate else None, st["vsum"] if approximate else None,
+                  st["hsum"] if approximate else None, idx, k_top, out=out, lse=lse, workspace=ws)
+    torch.cuda.synchronize()
+    assert not torch.isnan(out.float()).any(), "a query block was left out of the pairing"
+    assert not torch.isnan(lse).any()
+    rng = np.random.default_rng(9)
+    blocks = sorted(set([0, 1, N - 2, N - 1] + rng.choice(N, 22, replace=False).tolist()))
+    rows = rows_of_blocks(blocks, w.block, L)
+    for h in range(w.heads):
+        Q, K, V, st_ref, idx_ref, _ = oracle_head(q, k, v, h, w.block, scale, k_top)
+        idx_gpu = idx[0, h].cpu().numpy()
+        ref, ref_lse = po.attention_head(Q, K, V, w.block, idx_gpu, scale, "hybrid" if approximate else "sparse",
+                                         blocks=blocks, stats=st_ref)
+        rel, cos = row_errors(out[0, h].float().cpu().numpy()[rows], ref)
+        assert rel <= TOL[q.dtype] and cos >= COS_MIN, (h, rel, cos)
+        assert np.abs(lse[0, h].cpu().numpy()[rows] - ref_lse).max() <= 2e-2

@@ -27,6 +27,8 @@ def test_static_scratch_limit_is_enforced_on_the_host():
         n = -(-w.seq_len // w.block)
         npad = -(-n // 64) * 64
         need = w.batch * w.heads * (4 * npad * w.head_dim + 4 * w.head_dim ** 2)
+        if w.block == 64 and n >= 256:                   # scratch of the query-block pairing
+            need += w.batch * w.heads * (4 * n * -(-n // 32) + 32 * n + 8 * -(-n // 2))
         assert need <= pisa.STATIC_SCRATCH_BYTES, name
 
 
