@@ -168,6 +168,7 @@ int32_t pisa_select(const pisa_shape* shape, const double* qbar64, const double*
  * query blocks travel in one workgroup is decided from idx (blocks whose rows overlap most are
  * paired, three small launches ahead of the attention kernel), which changes the order of the
  * fp32 sums and nothing else; every entry point decides the same way for the same idx.
+ * (PISA_NO_PAIRING=1 in the environment, read once per process, keeps neighbours together.)
  */
 int32_t pisa_attention(const pisa_shape* shape, const void* q, const void* k, const void* v,
                        const float* kbar, const float* vsum, const float* hsum,

@@ -20,6 +20,8 @@
 //      blocks that propose to each other are paired), then the blocks still unmatched are
 //      paired in index order, and the pairs are written in the order of their lower member, so
 //      that consecutive workgroups still work on neighbouring parts of the sequence.
+#include <cstdlib>
+
 #include "common.h"
 
 namespace pisa {
@@ -204,7 +206,13 @@ bool pairing_pays(const Dims& dm, int k_top) {
   // block 64 only (a block-128 workgroup holds one block); on short sequences the launches cost
   // more than the shared tiles save, and above a density of 20 % neighbouring rows overlap so
   // much already that nothing was gained (measured at 25 % and 50 %)
-  return dm.dtype == PISA_BF16 && dm.B == kTile && k_top > 0 && k_top * 5 <= dm.N && dm.N >= 256;
+  // PISA_NO_PAIRING=1 in the environment (read once) keeps the neighbour pairing: for studies that
+  // need two launches to walk the same trips
+  static const bool off = [] {
+    const char* e = std::getenv("PISA_NO_PAIRING");
+    return e != nullptr && e[0] == '1';
+  }();
+  return !off && dm.dtype == PISA_BF16 && dm.B == kTile && k_top > 0 && k_top * 5 <= dm.N && dm.N >= 256;
 }
 
 size_t pairing_workspace_bytes(const Dims& dm) {

@@ -21,6 +21,7 @@ All print one JSON line per point.
 from __future__ import annotations
 
 import argparse
+import os
 import json
 
 import torch
@@ -151,7 +152,10 @@ def l2_miss_cost_study(args):
     """What the L2 misses of the exact phase cost at the Wan shape: pisa_attention on the real index sets
     against the same trip mix with every workgroup on one pair of rows (the same tiles for everybody, so all
     tile loads hit L2), each with the shader clock the chip holds meanwhile (the library's clock probe on a
-    second stream).  Under rocprofv3 --pmc the launches come in this order: real x (2 + reps), all-hit x (2 + reps)."""
+    second stream).  Under rocprofv3 --pmc the launches come in this order: real x (2 + reps), all-hit x (2 + reps).
+    The pairing of query blocks by row overlap is switched off for this process (it would put the identical rows
+    of the all-hit lists together), so both launches walk neighbour pairs."""
+    os.environ["PISA_NO_PAIRING"] = "1"            # read by the library at its first attention call
     dev = torch.device("cuda:0")
     w = WORKLOADS["wan"]
     q, k, v = make_qkv(w, device=dev)
