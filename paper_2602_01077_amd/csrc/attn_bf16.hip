@@ -72,10 +72,6 @@ template <int D> struct Geo {
 constexpr int QROWS = 128;                   // query rows per workgroup
 constexpr int MASK_WORDS = kMaxBlocks / 32;  // 128 words per block bitmask
 
-}  // namespace
-
-// Kernel parameters.  Not in the unnamed namespace: when this file is built as two translation
-// units (see PISA_ATTN_PART below) the launcher of one hands it to the other.
 struct PB {
   const __bf16* q;
   const __bf16* k;
@@ -91,8 +87,6 @@ struct PB {
   int first_order;
   const int32_t* pair;    // block 64 only, may be null: [bh][2 * n_super] query blocks of each workgroup (-1: none)
 };
-
-namespace {
 
 __device__ inline unsigned int pack_bf16(float lo, float hi) {
   f32x2 f = {lo, hi};
@@ -1030,28 +1024,12 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void attn_bf16_kernel(PB p) {
 
 }  // namespace
 
-// This file can be built as ONE translation unit (PISA_ATTN_PART undefined or 0) or as two:
-// part 1 holds the kernels that walk two tiles per block without a trip list (dense_attention
-// and block 128), part 2 everything else.  The library's build compiles part 1 with the
-// compiler's iterative instruction scheduler, which gains those kernels 3-5 % (measured) and
-// does nothing for the block-64 kernel at the paper's sparsities; the code is the same.
-#ifndef PISA_ATTN_PART
-#define PISA_ATTN_PART 0
-#endif
-
-template <int D> hipError_t launch_attention_two_tiles(const PB& p, bool dense, int grid, hipStream_t stream);
-
-#if PISA_ATTN_PART != 2
-template <int D> hipError_t launch_attention_two_tiles(const PB& p, bool dense, int grid, hipStream_t stream) {
+// The kernels that walk two tiles per block without a trip list: dense_attention and block 128.
+template <int D> static hipError_t launch_attention_two_tiles(const PB& p, bool dense, int grid, hipStream_t stream) {
   if (dense) hipLaunchKernelGGL((attn_bf16_kernel<D, true, 2>), dim3(grid), dim3(256), 0, stream, p);
   else hipLaunchKernelGGL((attn_bf16_kernel<D, false, 2>), dim3(grid), dim3(256), 0, stream, p);
   return hipGetLastError();
 }
-template hipError_t launch_attention_two_tiles<64>(const PB&, bool, int, hipStream_t);
-template hipError_t launch_attention_two_tiles<128>(const PB&, bool, int, hipStream_t);
-#endif
-
-#if PISA_ATTN_PART != 1
 
 size_t attention_workspace_bytes(const Dims& dm) {
   if (dm.dtype != PISA_BF16) return 0;
@@ -1148,7 +1126,5 @@ hipError_t static_scratch_ptr(void** out) {
 hipError_t launch_attention_bf16(const Dims& dm, const AttnArgs& a, hipStream_t stream) {
   return dm.d == 64 ? launch_attention_bf16_d<64>(dm, a, stream) : launch_attention_bf16_d<128>(dm, a, stream);
 }
-
-#endif  // PISA_ATTN_PART != 1
 
 }  // namespace pisa
