@@ -4,11 +4,13 @@
  * C ABI.  Every entry point below follows one step of the paper's forward-pass
  * algorithm (Methodology, "Hardware-aware Kernel Implementation", Alg. 1):
  *
- *   pisa_block_stats   Alg. 1, "Prepare" step   ("Prepare": block means, block value sums, global H)
- *   pisa_select        Alg. 1, "Select" step   (block-wise top-k of pooled scores)
- *   pisa_block_heterogeneity           ("Covariance-Aware Block Selection": log(M_j + eps))
- *   pisa_attention     Alg. 1, the loop over query blocks (its three phases) (Phase 1 exact, Phase 2 zeroth-order scan,
- *                                       Phase 3 global first-order term, one online softmax)
+ *   pisa_block_stats   Alg. 1, "Prepare" step (block means, block value sums, global H)
+ *   pisa_select        Alg. 1, "Select" step (block-wise top-k of pooled scores)
+ *   pisa_block_heterogeneity   "Covariance-Aware Block Selection": log(M_j + eps)
+ *   pisa_attention     Alg. 1, the loop over query blocks: Phase 1 exact, Phase 2 zeroth-order
+ *                      scan, Phase 3 global first-order term, one online softmax
+ *   pisa_attention_static      the same for callers that cannot allocate (built-in scratch)
+ *   pisa_forward       the three steps in one call (fewer launches on short sequences)
  *   dense_attention    Preliminaries, first equation (softmax(QK^T/sqrt d)V), the
  *                      speed-up baseline, written with the same tile loop
  *
